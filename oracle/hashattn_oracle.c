@@ -1,0 +1,308 @@
+/*
+ * CPU oracle for the HashAttention decode path.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, scalar implementation of what the path computes, written
+ * from the paper's definitions (arxiv 2412.14468):
+ *   - mapping  phi(x) = relu(sign(F(x))), bits packed into an integer (section 4.1, eq. 2)
+ *   - SCORE    Hamming distance as bitcount(xor) (section 4.1, eq. 1 and the
+ *              "Implementation" paragraph); used as the similarity 32 - H,
+ *              which orders tokens exactly as -H does
+ *   - TOPK     "standard top-k on these scores" (section 4)
+ *   - GATHER-ATT  softmax attention restricted to the index set (section 4)
+ *   - SDPA     single-query dense attention (section 3.1)
+ * All floating point is fp64.  No blocking, no fusion, no vectorisation.
+ * It shares no code with the HIP library; only tests, the smoke check and the
+ * benchmark's cpu_baseline leg may call it.  The product never does.
+ *
+ * Readings where the paper is silent (kept identical on the device side):
+ *   - sign(0) gives bit 0 (relu(sign(0)) = 0): bit_j = (a_j > 0)
+ *   - output unit j of F goes to bit j of the code (LSB = unit 0)
+ *   - hidden activation of F is SiLU; no activation before the sign
+ *   - ties in TOPK go to the lower token index; the set is returned ascending
+ *   - k_eff = min(k, N); softmax is max-subtracted; the scale is an argument
+ *   - phi_kv sees the key vector only (section 4.1, last paragraph)
+ *
+ * Pins: every function below is pinned by tests/test_oracle_*.py to brute
+ * force, closed forms or a library routine; none is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#define HA_BITS 32
+
+typedef struct {
+    int32_t n_heads;
+    int32_t n_layers;            /* number of weight matrices */
+    int32_t dims[5];             /* dims[0] = input dim, dims[n_layers] = 32 */
+    const float* W[4];           /* [n_heads][dims[l]][dims[l+1]], y = x W */
+    const float* bias[4];        /* [n_heads][dims[l+1]] or NULL */
+} ha_mlp;
+
+typedef struct {
+    uint16_t* k;                 /* bf16 bits; contiguous [B][Hkv][n_max][d] or paged [P][Hkv][page][d] */
+    uint16_t* v;
+    uint32_t* codes;             /* same layout without the d axis */
+    const int32_t* page_table;   /* [B][max_pages_per_seq], paged only */
+    int32_t* seq_lens;           /* [B] */
+    int64_t n_max;
+    int32_t max_pages_per_seq;
+    int32_t page_size;           /* 0 = contiguous */
+    int32_t n_kv_heads;
+    int32_t head_dim;
+} ha_cache;
+
+/* ---------------------------------------------------------------- helpers */
+
+static double bf16_to_double(uint16_t b)
+{
+    uint32_t u = ((uint32_t)b) << 16;
+    float f;
+    memcpy(&f, &u, sizeof f);
+    return (double)f;
+}
+
+/* index of token t's row (in rows, not bytes) for sequence b, KV head h */
+static int64_t row_of(const ha_cache* c, int b, int h, int64_t t)
+{
+    if (c->page_size == 0)
+        return ((int64_t)b * c->n_kv_heads + h) * c->n_max + t;
+    int64_t page = c->page_table[(int64_t)b * c->max_pages_per_seq + t / c->page_size];
+    return (page * c->n_kv_heads + h) * c->page_size + t % c->page_size;
+}
+
+int ha_oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------ mapping (section 4.1, eq. 2) */
+
+/* F(x) for one vector and one head, then sign -> bit, packed LSB-first.
+ * act (optional, 32 doubles) receives the pre-sign activations. */
+uint32_t ha_oracle_encode_vec(const ha_mlp* m, int head, const uint16_t* x_bf16, double* act)
+{
+    double cur[512], nxt[512];
+    int n_in = m->dims[0];
+    for (int i = 0; i < n_in; ++i) cur[i] = bf16_to_double(x_bf16[i]);
+    for (int l = 0; l < m->n_layers; ++l) {
+        int di = m->dims[l], dout = m->dims[l + 1];
+        const float* W = m->W[l] + (int64_t)head * di * dout;
+        for (int j = 0; j < dout; ++j) {
+            double z = 0.0;
+            for (int i = 0; i < di; ++i) z += cur[i] * (double)W[(int64_t)i * dout + j];
+            if (m->bias[l]) z += (double)m->bias[l][(int64_t)head * dout + j];
+            if (l + 1 < m->n_layers) z = z / (1.0 + exp(-z));   /* SiLU between layers */
+            nxt[j] = z;
+        }
+        memcpy(cur, nxt, sizeof(double) * dout);
+    }
+    uint32_t code = 0;
+    for (int j = 0; j < HA_BITS; ++j) {
+        if (act) act[j] = cur[j];
+        if (cur[j] > 0.0) code |= (uint32_t)1 << j;
+    }
+    return code;
+}
+
+/* q [B][Hq][d] bf16 -> q_codes [B][Hq], act [B][Hq][32] (optional) */
+void ha_oracle_encode_query(const ha_mlp* phi_q, const uint16_t* q, int batch, int d,
+                            uint32_t* q_codes, double* act)
+{
+    int H = phi_q->n_heads;
+    for (int b = 0; b < batch; ++b)
+        for (int h = 0; h < H; ++h) {
+            int64_t o = (int64_t)b * H + h;
+            q_codes[o] = ha_oracle_encode_vec(phi_q, h, q + o * d, act ? act + o * HA_BITS : NULL);
+        }
+}
+
+/* Key-code store update.
+ * k_new != NULL: append n_new tokens per sequence: rows k_new/v_new [B][Hkv][n_new][d] are
+ *   written at positions seq_lens[b] .. seq_lens[b]+n_new-1 together with their codes, then
+ *   seq_lens[b] += n_new.
+ * k_new == NULL: the rows are already in the cache; codes of the last min(n_new, seq_lens[b])
+ *   tokens of every sequence are (re)computed from the cached keys; seq_lens is unchanged.
+ * act (optional) receives pre-sign activations [B][Hkv][n_new][32] (slot j = j-th processed token). */
+void ha_oracle_encode_keys(const ha_mlp* phi_kv, ha_cache* c, const uint16_t* k_new,
+                           const uint16_t* v_new, int batch, int64_t n_new, double* act)
+{
+    int H = c->n_kv_heads, d = c->head_dim;
+    for (int b = 0; b < batch; ++b) {
+        int64_t len = c->seq_lens[b];
+        int64_t start = k_new ? len : (len > n_new ? len - n_new : 0);
+        int64_t cnt = k_new ? n_new : len - start;
+#pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < cnt; ++j) {
+            for (int h = 0; h < H; ++h) {
+                int64_t r = row_of(c, b, h, start + j);
+                if (k_new) {
+                    int64_t s = (((int64_t)b * H + h) * n_new + j) * d;
+                    memcpy(c->k + r * d, k_new + s, sizeof(uint16_t) * d);
+                    memcpy(c->v + r * d, v_new + s, sizeof(uint16_t) * d);
+                }
+                double* a = act ? act + (((int64_t)b * H + h) * n_new + j) * HA_BITS : NULL;
+                c->codes[r] = ha_oracle_encode_vec(phi_kv, h, c->k + r * d, a);
+            }
+        }
+        if (k_new) c->seq_lens[b] = (int32_t)(len + n_new);
+    }
+}
+
+/* ------------------------------------------------ SCORE (section 4.1, eq. 1) */
+
+/* similarity 32 - H(q, k), H = bitcount(xor) */
+int32_t ha_oracle_score(uint32_t q_code, uint32_t k_code)
+{
+    uint32_t x = q_code ^ k_code;
+    int32_t h = 0;
+    while (x) { h += (int32_t)(x & 1u); x >>= 1; }
+    return HA_BITS - h;
+}
+
+void ha_oracle_scores(uint32_t q_code, const uint32_t* k_codes, int64_t n, int32_t* scores)
+{
+    for (int64_t i = 0; i < n; ++i) scores[i] = ha_oracle_score(q_code, k_codes[i]);
+}
+
+/* ------------------------------------------------ TOPK (section 4) */
+
+typedef struct { int32_t score; int32_t id; } ha_pair;
+
+static int cmp_score_desc_id_asc(const void* a, const void* b)
+{
+    const ha_pair* x = (const ha_pair*)a;
+    const ha_pair* y = (const ha_pair*)b;
+    if (x->score != y->score) return (x->score > y->score) ? -1 : 1;
+    return (x->id > y->id) - (x->id < y->id);
+}
+
+static int cmp_i32(const void* a, const void* b)
+{
+    int32_t x = *(const int32_t*)a, y = *(const int32_t*)b;
+    return (x > y) - (x < y);
+}
+
+/* Definition: order all tokens by (score descending, index ascending), keep the first
+ * min(k, n), return them ascending by index.  Returns the count; *threshold (optional)
+ * gets the smallest selected score. */
+int64_t ha_oracle_topk_sort(const int32_t* scores, int64_t n, int64_t k, int32_t* idx, int32_t* threshold)
+{
+    int64_t ke = k < n ? k : n;
+    if (ke <= 0) return 0;
+    ha_pair* p = (ha_pair*)malloc(sizeof(ha_pair) * (size_t)n);
+    for (int64_t i = 0; i < n; ++i) { p[i].score = scores[i]; p[i].id = (int32_t)i; }
+    qsort(p, (size_t)n, sizeof(ha_pair), cmp_score_desc_id_asc);
+    if (threshold) *threshold = p[ke - 1].score;
+    for (int64_t i = 0; i < ke; ++i) idx[i] = p[i].id;
+    free(p);
+    qsort(idx, (size_t)ke, sizeof(int32_t), cmp_i32);
+    return ke;
+}
+
+/* Second, independent route to the same set: count tokens per score value, find the
+ * largest T with #{score >= T} >= k, take every token above T and the first
+ * k - #{score > T} tokens (in index order) that score exactly T. */
+int64_t ha_oracle_topk_hist(const int32_t* scores, int64_t n, int64_t k, int32_t* idx, int32_t* threshold)
+{
+    int64_t ke = k < n ? k : n;
+    if (ke <= 0) return 0;
+    int64_t hist[HA_BITS + 1];
+    memset(hist, 0, sizeof hist);
+    for (int64_t i = 0; i < n; ++i) hist[scores[i]]++;
+    int T = HA_BITS;
+    int64_t at_least = hist[HA_BITS];        /* #{score >= T} */
+    while (at_least < ke) { --T; at_least += hist[T]; }
+    int64_t above = at_least - hist[T];      /* #{score > T} */
+    int64_t quota = ke - above;              /* tokens taken from the tie bucket */
+    int64_t out = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        if (scores[i] > T) idx[out++] = (int32_t)i;
+        else if (scores[i] == T && quota > 0) { idx[out++] = (int32_t)i; --quota; }
+    }
+    if (threshold) *threshold = T;
+    return out;
+}
+
+/* ------------------------------------------------ GATHER-ATT and SDPA (sections 3.1, 4) */
+
+/* o = sum_{i in I} softmax_i(scale <q, k_i>) v_i over the rows listed in idx (logical token ids
+ * of sequence b, KV head h).  out: d doubles.  cnt == 0 gives zeros. */
+void ha_oracle_gather_attend(const ha_cache* c, int b, int h, const uint16_t* q_bf16,
+                             const int32_t* idx, int64_t cnt, double scale, double* out)
+{
+    int d = c->head_dim;
+    for (int j = 0; j < d; ++j) out[j] = 0.0;
+    if (cnt <= 0) return;
+    double* logit = (double*)malloc(sizeof(double) * (size_t)cnt);
+    double m = -INFINITY;
+    for (int64_t i = 0; i < cnt; ++i) {
+        const uint16_t* kr = c->k + row_of(c, b, h, idx[i]) * d;
+        double s = 0.0;
+        for (int j = 0; j < d; ++j) s += bf16_to_double(q_bf16[j]) * bf16_to_double(kr[j]);
+        logit[i] = s * scale;
+        if (logit[i] > m) m = logit[i];
+    }
+    double denom = 0.0;
+    for (int64_t i = 0; i < cnt; ++i) {
+        double w = exp(logit[i] - m);
+        const uint16_t* vr = c->v + row_of(c, b, h, idx[i]) * d;
+        denom += w;
+        for (int j = 0; j < d; ++j) out[j] += w * bf16_to_double(vr[j]);
+    }
+    for (int j = 0; j < d; ++j) out[j] /= denom;
+    free(logit);
+}
+
+/* single-query SDPA over all n tokens: the index set is {0..n-1} */
+void ha_oracle_dense_attend(const ha_cache* c, int b, int h, const uint16_t* q_bf16,
+                            int64_t n, double scale, double* out)
+{
+    int32_t* all = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    for (int64_t i = 0; i < n; ++i) all[i] = (int32_t)i;
+    ha_oracle_gather_attend(c, b, h, q_bf16, all, n, scale, out);
+    free(all);
+}
+
+/* ------------------------------------------------ one decode layer-step */
+
+/* [append] -> encode query -> SCORE -> TOPK (full sort) -> GATHER-ATT for every
+ * (sequence, query head); KV head of query head h is h / (Hq / Hkv).
+ * k_new/v_new: [B][Hkv][d] or NULL (no append).  k_per_seq [B].
+ * phi_q == NULL: q_codes [B][Hq] is an input (codes drawn directly, no mapping).
+ * Outputs: q_codes [B][Hq]; idx [B][Hq][k_max]; count [B][Hq]; threshold [B][Hq];
+ * out [B][Hq][d] doubles.  Heads are independent, so the (b, h) loop may run on
+ * several threads; each iteration is the plain single-head computation. */
+void ha_oracle_decode_step(const ha_mlp* phi_q, const ha_mlp* phi_kv, ha_cache* c,
+                           const uint16_t* q, const uint16_t* k_new, const uint16_t* v_new,
+                           int batch, int n_q_heads, const int32_t* k_per_seq, int64_t k_max,
+                           double scale, uint32_t* q_codes, int32_t* idx, int32_t* count,
+                           int32_t* threshold, double* out)
+{
+    int d = c->head_dim, Hq = n_q_heads, g = Hq / c->n_kv_heads;
+    if (k_new) ha_oracle_encode_keys(phi_kv, c, k_new, v_new, batch, 1, NULL);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t bh = 0; bh < (int64_t)batch * Hq; ++bh) {
+        int b = (int)(bh / Hq), h = (int)(bh % Hq), hk = h / g;
+        int64_t n = c->seq_lens[b];
+        const uint16_t* qv = q + bh * d;
+        if (phi_q) q_codes[bh] = ha_oracle_encode_vec(phi_q, h, qv, NULL);   /* else: given */
+        int32_t* scores = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+        for (int64_t t = 0; t < n; ++t)
+            scores[t] = ha_oracle_score(q_codes[bh], c->codes[row_of(c, b, hk, t)]);
+        int32_t T = 0;
+        int64_t cnt = ha_oracle_topk_sort(scores, n, k_per_seq[b], idx + bh * k_max, &T);
+        count[bh] = (int32_t)cnt;
+        threshold[bh] = T;
+        ha_oracle_gather_attend(c, b, hk, qv, idx + bh * k_max, cnt, scale, out + bh * d);
+        free(scores);
+    }
+}
