@@ -1,0 +1,168 @@
+/*
+ * hashattn.h - C ABI of the MI355X (gfx950) HashAttention decode library.
+ *
+ * One decode layer-step of HashAttention (arxiv 2412.14468, section 4):
+ *     [append new token]  ->  encode query  ->  SCORE  ->  TOPK  ->  GATHER-ATT
+ *
+ * Conventions that hold for every call
+ *   - "dev" pointers are DEVICE pointers owned by the caller.  The library
+ *     never frees, reallocates or keeps them after the call returns.  "host"
+ *     pointers are ordinary host memory.  Structs are passed by host pointer
+ *     and may hold device pointers; they are read during the call only.
+ *   - Work is enqueued on the caller's HIP stream (`stream`, a hipStream_t
+ *     passed as void*; NULL = the default stream) and the call returns without
+ *     synchronising.  Nothing is copied to the host.
+ *   - A context owns only the library's scratch memory (histograms, offsets,
+ *     split partials), sized at creation from the max_* fields.  Calls that
+ *     use one context must not overlap in time (same stream, or ordered
+ *     streams): they share that scratch.
+ *   - Errors are return codes; arguments are checked on the host before any
+ *     launch, so a call that returns an error has enqueued nothing.
+ *     hashattn_last_error() gives a readable message for the last failure on
+ *     that context (or of hashattn_create when ctx == NULL).
+ *   - bf16 tensors are 16-bit brain floats; head_dim is 128; codes have 32
+ *     bits.  Query head h uses KV head h / (n_q_heads / n_kv_heads).
+ *   - Bit order of a code: output unit j of the mapping network is bit j
+ *     (least significant bit = unit 0); bit = 1 iff the activation is > 0
+ *     (phi(x) = relu(sign(F(x))), section 4.1, eq. 2; sign(0) gives 0).
+ *   - Token t of sequence b, KV head h lives at row
+ *       contiguous:  (b * n_kv_heads + h) * n_max + t
+ *       paged:       (page_table[b][t / page_size] * n_kv_heads + h) * page_size + t % page_size
+ *     in k, v (rows of head_dim bf16) and in codes (one uint32 per row).
+ */
+#ifndef HASHATTN_H
+#define HASHATTN_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hashattn_ctx hashattn_ctx;
+
+typedef int32_t hashattn_status;
+enum {
+    HASHATTN_OK = 0,
+    HASHATTN_INVALID_ARG = 1,       /* NULL pointer, bad size, misalignment, limit exceeded */
+    HASHATTN_UNSUPPORTED = 2,       /* shape the kernels are not written for */
+    HASHATTN_SCRATCH_TOO_SMALL = 3, /* call exceeds the max_* the context was created with */
+    HASHATTN_HIP_ERROR = 4          /* a HIP runtime call failed */
+};
+
+/* Limits and shape of the attention layer a context serves. */
+typedef struct {
+    int32_t head_dim;      /* must be 128 */
+    int32_t n_q_heads;     /* multiple of n_kv_heads; group size 1, 2, 4 or 8 */
+    int32_t n_kv_heads;
+    int32_t bits;          /* must be 32 */
+    int32_t page_size;     /* 0 = contiguous KV cache, 16 = paged */
+    int32_t max_batch;
+    int64_t max_context;   /* largest sequence length any call will see */
+    int64_t max_k;         /* largest k any call will ask for */
+} hashattn_config;
+
+/* Mapping network F of phi (section 4.1, eq. 2): n_layers weight matrices with
+ * SiLU between them and no activation before the sign.  Layer l maps dims[l]
+ * inputs to dims[l+1] outputs as y = x W (+ bias).  dims[0] = 128, hidden
+ * widths <= 256 and multiples of 32, dims[n_layers] = 32.  One network per head. */
+typedef struct {
+    int32_t n_heads;
+    int32_t n_layers;         /* 1, 2 or 3 */
+    int32_t dims[5];
+    const float* W[4];        /* dev fp32, [n_heads][dims[l]][dims[l+1]] row-major */
+    const float* bias[4];     /* dev fp32, [n_heads][dims[l+1]], or NULL */
+} hashattn_mlp;
+
+/* KV cache with its key-code store (32 bits per token per KV head, section 4.1
+ * "Implementation").  All device memory belongs to the caller. */
+typedef struct {
+    void* k;                  /* dev bf16: contiguous [B][H_kv][n_max][128] | paged [P][H_kv][16][128] */
+    void* v;                  /* dev bf16, same layout */
+    uint32_t* codes;          /* dev: contiguous [B][H_kv][n_max] | paged [P][H_kv][16] */
+    const int32_t* page_table;/* dev [B][max_pages_per_seq] physical page ids; paged only, else NULL */
+    int32_t* seq_lens;        /* dev [B] current length of every sequence */
+    int64_t n_max;            /* contiguous: row capacity per (b, head), a multiple of 4; paged: ignored */
+    int64_t n_pages;          /* paged: number of physical pages P; contiguous: ignored */
+    int32_t max_pages_per_seq;/* paged only */
+    int32_t max_seq_len;      /* HOST upper bound on seq_lens[*] valid for this call (sizes the grids);
+                                 hashattn_encode_keys in append mode adds n_new to it */
+} hashattn_kv;
+
+/* Create / destroy a context on the current HIP device.  Allocates scratch
+ * with hipMalloc (a few MB for the Llama-3.1-8B shape at 512K context). */
+hashattn_status hashattn_create(hashattn_ctx** ctx, const hashattn_config* cfg);
+hashattn_status hashattn_destroy(hashattn_ctx* ctx);
+const char* hashattn_last_error(const hashattn_ctx* ctx);
+/* Bytes of device scratch the context holds. */
+int64_t hashattn_scratch_bytes(const hashattn_ctx* ctx);
+
+/* Key signatures phi_int,kv(k), "computed and cached along with KV Cache"
+ * (section 4.1, Implementation; phi_kv reads the key vector only).
+ *   append mode (k_new, v_new != NULL): k_new, v_new are dev bf16
+ *     [batch][H_kv][n_new][128].  For every sequence b the n_new rows are
+ *     written at positions seq_lens[b] .. seq_lens[b]+n_new-1 of the cache
+ *     together with their codes, then seq_lens[b] += n_new (on the device) and
+ *     cache->max_seq_len += n_new (on the host).  Needs max_seq_len + n_new <=
+ *     n_max (contiguous) or <= max_pages_per_seq * 16 (paged; the page table
+ *     must already map the new positions).
+ *   in-place mode (k_new == NULL, v_new == NULL): the rows are already in the
+ *     cache; the codes of the last min(n_new, seq_lens[b]) tokens of every
+ *     sequence are recomputed from the cached keys.  seq_lens is unchanged.
+ *     n_new = max_seq_len rebuilds the whole store (prefill). */
+hashattn_status hashattn_encode_keys(hashattn_ctx* ctx, const hashattn_mlp* phi_kv,
+                                     const void* k_new, const void* v_new,
+                                     int32_t batch, int64_t n_new,
+                                     hashattn_kv* cache, void* stream);
+
+/* Query signatures phi_int,q(q) (section 4.1, eq. 2), one network per query head.
+ *   q        dev bf16 [batch][n_q_heads][128]
+ *   q_codes  dev uint32 [batch][n_q_heads] (output) */
+hashattn_status hashattn_encode_query(hashattn_ctx* ctx, const hashattn_mlp* phi_q,
+                                      const void* q, int32_t batch,
+                                      uint32_t* q_codes, void* stream);
+
+/* SCORE + TOPK (section 4; section 4.1, eq. 1).  The score of token i for
+ * query head h is the Hamming similarity 32 - bitcount(q_code XOR k_code_i),
+ * which orders tokens exactly as -Hamming distance does.  For every (b, h) the
+ * k_eff = min(k_b, seq_lens[b]) best tokens are selected; among equal scores
+ * the lower token index wins.
+ *   q_codes    dev uint32 [batch][n_q_heads]
+ *   k_per_seq  dev int32 [batch], or NULL for k_max everywhere
+ *   k_max      host upper bound on every k_b (>= 1, <= max_k); row pitch of idx
+ *   idx        dev int32 [batch][n_q_heads][k_max] (output): logical token ids,
+ *              ascending; slots >= count are left untouched
+ *   count      dev int32 [batch][n_q_heads] (output): k_eff (0 for an empty sequence)
+ *   threshold  dev uint8 [batch][n_q_heads] (output) or NULL: smallest selected score */
+hashattn_status hashattn_score_topk(hashattn_ctx* ctx, const uint32_t* q_codes,
+                                    const hashattn_kv* cache, int32_t batch,
+                                    const int32_t* k_per_seq, int32_t k_max,
+                                    int32_t* idx, int32_t* count, uint8_t* threshold,
+                                    void* stream);
+
+/* GATHER-ATT (section 4): softmax attention over the selected tokens only,
+ *   out[b][h] = sum_{i in I} softmax_i(scale * <q, k_i>) v_i,
+ * normalised over the selected tokens, fp32 accumulation, bf16 result.
+ *   q      dev bf16 [batch][n_q_heads][128]
+ *   idx    dev int32 [batch][n_q_heads][k_max]: logical token ids, unique and
+ *          < seq_lens[b] (not checked on the device)
+ *   count  dev int32 [batch][n_q_heads]: entries of idx in use (<= k_max);
+ *          0 gives a zero output row
+ *   scale  softmax scale, 1/sqrt(128) for SDPA (section 3.1)
+ *   out    dev bf16 [batch][n_q_heads][128] (output) */
+hashattn_status hashattn_gather_attend(hashattn_ctx* ctx, const void* q,
+                                       const hashattn_kv* cache, const int32_t* idx,
+                                       const int32_t* count, int32_t batch, int32_t k_max,
+                                       float scale, void* out, void* stream);
+
+/* Dense single-query SDPA over all seq_lens[b] tokens (section 3.1), GQA-aware
+ * (K/V rows are read once per KV head).  The in-house dense decode kernel the
+ * sparse path is compared against; same q/out layout as hashattn_gather_attend. */
+hashattn_status hashattn_dense_attend(hashattn_ctx* ctx, const void* q,
+                                      const hashattn_kv* cache, int32_t batch,
+                                      float scale, void* out, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HASHATTN_H */

@@ -1,0 +1,340 @@
+// C ABI of the HashAttention decode library: argument checks, scratch
+// ownership, launch-shape choices.  All arithmetic is in the kernels.
+#include "../../include/hashattn.h"
+#include "kernels.hpp"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+struct hashattn_ctx {
+    hashattn_config cfg;
+    int device;
+    int group;
+    // TOPK scratch
+    uint16_t* unit_hist;
+    int2* unit_off;
+    int2* sel;
+    int32_t units_pitch;
+    // split partials shared by GATHER-ATT and the dense kernel
+    float* part;
+    int64_t part_floats;
+    int64_t scratch_bytes;
+    char err[256];
+};
+
+namespace {
+
+constexpr int kMinUnit = 256;          // tokens per wave unit: one 16-byte load per lane
+constexpr int kMaxUnit = 16384;        // keeps per-unit counts inside uint16
+constexpr int kMaxSplits = 256;
+
+char g_create_err[256] = "";
+
+hashattn_status fail(hashattn_ctx* ctx, hashattn_status st, const char* fmt, ...)
+{
+    char* dst = ctx ? ctx->err : g_create_err;
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(dst, 256, fmt, ap);
+    va_end(ap);
+    return st;
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+bool pow2_width(int w) { return w == 32 || w == 64 || w == 128 || w == 256; }
+
+hashattn_status check_mlp(hashattn_ctx* ctx, const hashattn_mlp* m, int n_heads, const char* what)
+{
+    if (!m) return fail(ctx, HASHATTN_INVALID_ARG, "%s: mapping network is NULL", what);
+    if (m->n_heads != n_heads)
+        return fail(ctx, HASHATTN_INVALID_ARG, "%s: network has %d heads, expected %d", what, m->n_heads, n_heads);
+    if (m->n_layers < 1 || m->n_layers > 3)
+        return fail(ctx, HASHATTN_UNSUPPORTED, "%s: n_layers %d not in 1..3", what, m->n_layers);
+    if (m->dims[0] != ha::kHeadDim || m->dims[m->n_layers] != ha::kBits)
+        return fail(ctx, HASHATTN_UNSUPPORTED, "%s: network must map 128 inputs to 32 outputs", what);
+    for (int l = 1; l < m->n_layers; ++l)
+        if (!pow2_width(m->dims[l]))
+            return fail(ctx, HASHATTN_UNSUPPORTED, "%s: hidden width %d not in {32,64,128,256}", what, m->dims[l]);
+    for (int l = 0; l < m->n_layers; ++l) {
+        if (!m->W[l]) return fail(ctx, HASHATTN_INVALID_ARG, "%s: W[%d] is NULL", what, l);
+        if (!aligned(m->W[l], 16)) return fail(ctx, HASHATTN_INVALID_ARG, "%s: W[%d] not 16-byte aligned", what, l);
+        if (m->bias[l] && !aligned(m->bias[l], 4))
+            return fail(ctx, HASHATTN_INVALID_ARG, "%s: bias[%d] not 4-byte aligned", what, l);
+    }
+    return HASHATTN_OK;
+}
+
+ha::MlpView view_of(const hashattn_mlp* m)
+{
+    ha::MlpView v{};
+    v.n_layers = m->n_layers;
+    for (int i = 0; i < 5; ++i) v.dims[i] = m->dims[i];
+    for (int i = 0; i < 4; ++i) { v.W[i] = i < m->n_layers ? m->W[i] : nullptr; v.bias[i] = i < m->n_layers ? m->bias[i] : nullptr; }
+    return v;
+}
+
+hashattn_status check_cache(hashattn_ctx* ctx, const hashattn_kv* kv, int batch, bool need_codes, const char* what)
+{
+    if (!kv) return fail(ctx, HASHATTN_INVALID_ARG, "%s: cache is NULL", what);
+    if (batch < 1) return fail(ctx, HASHATTN_INVALID_ARG, "%s: batch %d < 1", what, batch);
+    if (batch > ctx->cfg.max_batch)
+        return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "%s: batch %d exceeds max_batch %d", what, batch, ctx->cfg.max_batch);
+    if (!kv->k || !kv->v || !kv->seq_lens) return fail(ctx, HASHATTN_INVALID_ARG, "%s: k, v or seq_lens is NULL", what);
+    if (need_codes && !kv->codes) return fail(ctx, HASHATTN_INVALID_ARG, "%s: codes is NULL", what);
+    if (!aligned(kv->k, 16) || !aligned(kv->v, 16)) return fail(ctx, HASHATTN_INVALID_ARG, "%s: k/v not 16-byte aligned", what);
+    if (kv->codes && !aligned(kv->codes, 16)) return fail(ctx, HASHATTN_INVALID_ARG, "%s: codes not 16-byte aligned", what);
+    if (!aligned(kv->seq_lens, 4)) return fail(ctx, HASHATTN_INVALID_ARG, "%s: seq_lens not 4-byte aligned", what);
+    if (kv->max_seq_len < 0) return fail(ctx, HASHATTN_INVALID_ARG, "%s: max_seq_len %d < 0", what, kv->max_seq_len);
+    if (kv->max_seq_len > ctx->cfg.max_context)
+        return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "%s: max_seq_len %d exceeds max_context %lld", what,
+                    kv->max_seq_len, (long long)ctx->cfg.max_context);
+    if (ctx->cfg.page_size == 0) {
+        if (kv->page_table) return fail(ctx, HASHATTN_INVALID_ARG, "%s: page_table given to a contiguous context", what);
+        if (kv->n_max < 1 || (kv->n_max & 3)) return fail(ctx, HASHATTN_INVALID_ARG, "%s: n_max %lld must be a positive multiple of 4", what, (long long)kv->n_max);
+        if (kv->max_seq_len > kv->n_max) return fail(ctx, HASHATTN_INVALID_ARG, "%s: max_seq_len %d exceeds n_max %lld", what, kv->max_seq_len, (long long)kv->n_max);
+    } else {
+        if (!kv->page_table) return fail(ctx, HASHATTN_INVALID_ARG, "%s: page_table is NULL in a paged context", what);
+        if (!aligned(kv->page_table, 4)) return fail(ctx, HASHATTN_INVALID_ARG, "%s: page_table not 4-byte aligned", what);
+        if (kv->max_pages_per_seq < 1 || kv->n_pages < 1) return fail(ctx, HASHATTN_INVALID_ARG, "%s: max_pages_per_seq and n_pages must be >= 1", what);
+        if ((int64_t)kv->max_seq_len > (int64_t)kv->max_pages_per_seq * ha::kPage)
+            return fail(ctx, HASHATTN_INVALID_ARG, "%s: max_seq_len %d exceeds the page table's reach", what, kv->max_seq_len);
+    }
+    return HASHATTN_OK;
+}
+
+ha::KvView view_of(const hashattn_ctx* ctx, const hashattn_kv* kv)
+{
+    ha::KvView v{};
+    v.k = static_cast<const uint16_t*>(kv->k);
+    v.v = static_cast<const uint16_t*>(kv->v);
+    v.codes = kv->codes;
+    v.page_table = kv->page_table;
+    v.seq_lens = kv->seq_lens;
+    v.n_max = kv->n_max;
+    v.max_pages_per_seq = kv->max_pages_per_seq;
+    v.n_kv_heads = ctx->cfg.n_kv_heads;
+    return v;
+}
+
+// Tokens per wave unit of SCORE/TOPK: small units fill the chip at short contexts, larger ones
+// keep the number of per-unit histograms down at long contexts.
+int pick_unit_tokens(const hashattn_ctx* ctx, int batch, int max_seq_len)
+{
+    const int64_t lanes = (int64_t)batch * ctx->cfg.n_kv_heads;
+    int unit = kMinUnit;
+    // aim for about 8192 waves in flight over the whole grid, never more units than the scratch pitch
+    while (unit < kMaxUnit &&
+           (lanes * ((max_seq_len + unit - 1) / unit) > 8192 ||
+            (max_seq_len + unit - 1) / unit > ctx->units_pitch))
+        unit *= 2;
+    return unit;
+}
+
+// Split shape for the attention kernels: `total` tokens per (sequence, head), `lanes` independent
+// (sequence, head) pairs that share the launch.
+void pick_splits(const hashattn_ctx* ctx, int64_t lanes, int64_t total, int batch, int* chunk, int* n_splits)
+{
+    int64_t cap = ctx->part_floats / ((int64_t)batch * ctx->cfg.n_q_heads * ha::kPartStride);
+    if (cap > kMaxSplits) cap = kMaxSplits;
+    if (cap < 1) cap = 1;
+    int64_t want = (2048 + lanes - 1) / lanes;                 // about 8 blocks per CU over the grid
+    if (want > cap) want = cap;
+    if (want < 1) want = 1;
+    int64_t c = (total + want - 1) / want;
+    c = (c + 63) / 64 * 64;                                    // whole 64-row iterations
+    if (c < 64) c = 64;
+    int64_t s = (total + c - 1) / c;
+    if (s < 1) s = 1;
+    while (s > cap) { c *= 2; s = (total + c - 1) / c; }
+    *chunk = (int)c;
+    *n_splits = (int)s;
+}
+
+hashattn_status hip_fail(hashattn_ctx* ctx, hipError_t e, const char* what)
+{
+    return fail(ctx, HASHATTN_HIP_ERROR, "%s: %s", what, hipGetErrorString(e));
+}
+
+}  // namespace
+
+extern "C" {
+
+hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
+{
+    if (!out || !cfg) return fail(nullptr, HASHATTN_INVALID_ARG, "create: NULL argument");
+    *out = nullptr;
+    if (cfg->head_dim != ha::kHeadDim) return fail(nullptr, HASHATTN_UNSUPPORTED, "create: head_dim %d, only 128 is supported", cfg->head_dim);
+    if (cfg->bits != ha::kBits) return fail(nullptr, HASHATTN_UNSUPPORTED, "create: bits %d, only 32 is supported", cfg->bits);
+    if (cfg->n_kv_heads < 1 || cfg->n_q_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads)
+        return fail(nullptr, HASHATTN_INVALID_ARG, "create: n_q_heads %d must be a positive multiple of n_kv_heads %d", cfg->n_q_heads, cfg->n_kv_heads);
+    const int group = cfg->n_q_heads / cfg->n_kv_heads;
+    if (group != 1 && group != 2 && group != 4 && group != 8)
+        return fail(nullptr, HASHATTN_UNSUPPORTED, "create: group size %d not in {1,2,4,8}", group);
+    if (cfg->page_size != 0 && cfg->page_size != ha::kPage)
+        return fail(nullptr, HASHATTN_UNSUPPORTED, "create: page_size %d, only 0 (contiguous) or 16", cfg->page_size);
+    if (cfg->max_batch < 1 || cfg->max_batch > 65535) return fail(nullptr, HASHATTN_INVALID_ARG, "create: max_batch %d not in 1..65535", cfg->max_batch);
+    if (cfg->max_context < 1 || cfg->max_context > (int64_t)1 << 30)
+        return fail(nullptr, HASHATTN_INVALID_ARG, "create: max_context %lld not in 1..2^30", (long long)cfg->max_context);
+    if (cfg->max_k < 1 || cfg->max_k > (int64_t)1 << 30)
+        return fail(nullptr, HASHATTN_INVALID_ARG, "create: max_k %lld not in 1..2^30", (long long)cfg->max_k);
+    if (cfg->n_kv_heads > 65535) return fail(nullptr, HASHATTN_INVALID_ARG, "create: n_kv_heads too large");
+
+    hashattn_ctx* ctx = new (std::nothrow) hashattn_ctx();
+    if (!ctx) return fail(nullptr, HASHATTN_HIP_ERROR, "create: out of host memory");
+    ctx->cfg = *cfg;
+    ctx->group = group;
+    ctx->err[0] = 0;
+    hipError_t e = hipGetDevice(&ctx->device);
+    if (e != hipSuccess) { delete ctx; return fail(nullptr, HASHATTN_HIP_ERROR, "create: hipGetDevice: %s", hipGetErrorString(e)); }
+
+    const int64_t bh = (int64_t)cfg->max_batch * cfg->n_q_heads;
+    // unit pitch: enough 256-token units for max_context, capped so that the per-unit histograms stay small
+    int64_t pitch = (cfg->max_context + kMinUnit - 1) / kMinUnit;
+    const int64_t min_pitch = (cfg->max_context + kMaxUnit - 1) / kMaxUnit;
+    const int64_t budget = (int64_t)(64 << 20) / (bh * ha::kBins * (int64_t)sizeof(uint16_t));   // 64 MiB of histograms
+    if (pitch > budget) pitch = budget;
+    if (pitch < min_pitch) pitch = min_pitch;
+    pitch = (pitch + 7) / 8 * 8;
+    ctx->units_pitch = (int32_t)pitch;
+    const int64_t hist_bytes = bh * ha::kBins * pitch * (int64_t)sizeof(uint16_t);
+    const int64_t off_bytes = bh * pitch * (int64_t)sizeof(int2);
+    const int64_t sel_bytes = bh * (int64_t)sizeof(int2);
+    int64_t splits = (cfg->max_context + 63) / 64;               // dense needs more splits than gather
+    int64_t want = 4096 / bh; if (want < 8) want = 8;
+    if (splits > want) splits = want;
+    if (splits > kMaxSplits) splits = kMaxSplits;
+    ctx->part_floats = bh * splits * ha::kPartStride;
+    const int64_t part_bytes = ctx->part_floats * (int64_t)sizeof(float);
+    ctx->scratch_bytes = hist_bytes + off_bytes + sel_bytes + part_bytes;
+
+    if ((e = hipMalloc(reinterpret_cast<void**>(&ctx->unit_hist), hist_bytes)) != hipSuccess ||
+        (e = hipMalloc(reinterpret_cast<void**>(&ctx->unit_off), off_bytes)) != hipSuccess ||
+        (e = hipMalloc(reinterpret_cast<void**>(&ctx->sel), sel_bytes)) != hipSuccess ||
+        (e = hipMalloc(reinterpret_cast<void**>(&ctx->part), part_bytes)) != hipSuccess) {
+        hashattn_destroy(ctx);
+        return fail(nullptr, HASHATTN_HIP_ERROR, "create: hipMalloc of %lld scratch bytes: %s",
+                    (long long)ctx->scratch_bytes, hipGetErrorString(e));
+    }
+    *out = ctx;
+    return HASHATTN_OK;
+}
+
+hashattn_status hashattn_destroy(hashattn_ctx* ctx)
+{
+    if (!ctx) return HASHATTN_OK;
+    if (ctx->unit_hist) (void)hipFree(ctx->unit_hist);
+    if (ctx->unit_off) (void)hipFree(ctx->unit_off);
+    if (ctx->sel) (void)hipFree(ctx->sel);
+    if (ctx->part) (void)hipFree(ctx->part);
+    delete ctx;
+    return HASHATTN_OK;
+}
+
+const char* hashattn_last_error(const hashattn_ctx* ctx) { return ctx ? ctx->err : g_create_err; }
+
+int64_t hashattn_scratch_bytes(const hashattn_ctx* ctx) { return ctx ? ctx->scratch_bytes : 0; }
+
+hashattn_status hashattn_encode_keys(hashattn_ctx* ctx, const hashattn_mlp* phi_kv, const void* k_new,
+                                     const void* v_new, int32_t batch, int64_t n_new, hashattn_kv* cache,
+                                     void* stream)
+{
+    if (!ctx) return HASHATTN_INVALID_ARG;
+    if (hashattn_status s = check_mlp(ctx, phi_kv, ctx->cfg.n_kv_heads, "encode_keys")) return s;
+    if (hashattn_status s = check_cache(ctx, cache, batch, true, "encode_keys")) return s;
+    if ((k_new == nullptr) != (v_new == nullptr))
+        return fail(ctx, HASHATTN_INVALID_ARG, "encode_keys: k_new and v_new must both be given (append) or both NULL (in place)");
+    if (n_new < 1) return fail(ctx, HASHATTN_INVALID_ARG, "encode_keys: n_new %lld < 1", (long long)n_new);
+    const bool paged = ctx->cfg.page_size != 0;
+    if (k_new) {
+        if (!aligned(k_new, 16) || !aligned(v_new, 16)) return fail(ctx, HASHATTN_INVALID_ARG, "encode_keys: k_new/v_new not 16-byte aligned");
+        const int64_t room = paged ? (int64_t)cache->max_pages_per_seq * ha::kPage : cache->n_max;
+        if ((int64_t)cache->max_seq_len + n_new > room)
+            return fail(ctx, HASHATTN_INVALID_ARG, "encode_keys: appending %lld tokens to max_seq_len %d exceeds the cache capacity %lld",
+                        (long long)n_new, cache->max_seq_len, (long long)room);
+        if ((int64_t)cache->max_seq_len + n_new > ctx->cfg.max_context)
+            return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "encode_keys: append would exceed max_context %lld", (long long)ctx->cfg.max_context);
+    }
+    const hipError_t e = ha::launch_encode_keys(view_of(phi_kv), view_of(ctx, cache), paged,
+                                                static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
+                                                batch, n_new, cache->max_seq_len, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(ctx, e, "encode_keys");
+    if (k_new) cache->max_seq_len += (int32_t)n_new;
+    return HASHATTN_OK;
+}
+
+hashattn_status hashattn_encode_query(hashattn_ctx* ctx, const hashattn_mlp* phi_q, const void* q, int32_t batch,
+                                      uint32_t* q_codes, void* stream)
+{
+    if (!ctx) return HASHATTN_INVALID_ARG;
+    if (hashattn_status s = check_mlp(ctx, phi_q, ctx->cfg.n_q_heads, "encode_query")) return s;
+    if (!q || !q_codes) return fail(ctx, HASHATTN_INVALID_ARG, "encode_query: q or q_codes is NULL");
+    if (!aligned(q, 16) || !aligned(q_codes, 4)) return fail(ctx, HASHATTN_INVALID_ARG, "encode_query: q needs 16-byte, q_codes 4-byte alignment");
+    if (batch < 1) return fail(ctx, HASHATTN_INVALID_ARG, "encode_query: batch %d < 1", batch);
+    if (batch > ctx->cfg.max_batch) return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "encode_query: batch %d exceeds max_batch %d", batch, ctx->cfg.max_batch);
+    const hipError_t e = ha::launch_encode_query(view_of(phi_q), static_cast<const uint16_t*>(q), batch,
+                                                 ctx->cfg.n_q_heads, q_codes, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HASHATTN_OK : hip_fail(ctx, e, "encode_query");
+}
+
+hashattn_status hashattn_score_topk(hashattn_ctx* ctx, const uint32_t* q_codes, const hashattn_kv* cache,
+                                    int32_t batch, const int32_t* k_per_seq, int32_t k_max, int32_t* idx,
+                                    int32_t* count, uint8_t* threshold, void* stream)
+{
+    if (!ctx) return HASHATTN_INVALID_ARG;
+    if (hashattn_status s = check_cache(ctx, cache, batch, true, "score_topk")) return s;
+    if (!q_codes || !idx || !count) return fail(ctx, HASHATTN_INVALID_ARG, "score_topk: q_codes, idx or count is NULL");
+    if (!aligned(q_codes, 4) || !aligned(idx, 4) || !aligned(count, 4) || (k_per_seq && !aligned(k_per_seq, 4)))
+        return fail(ctx, HASHATTN_INVALID_ARG, "score_topk: 4-byte alignment required");
+    if (k_max < 1) return fail(ctx, HASHATTN_INVALID_ARG, "score_topk: k_max %d < 1", k_max);
+    if (k_max > ctx->cfg.max_k) return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "score_topk: k_max %d exceeds max_k %lld", k_max, (long long)ctx->cfg.max_k);
+    const ha::TopkScratch sc{ctx->unit_hist, ctx->unit_off, ctx->sel, ctx->units_pitch};
+    const int unit = pick_unit_tokens(ctx, batch, cache->max_seq_len);
+    const hipError_t e = ha::launch_score_topk(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group, q_codes, batch,
+                                               ctx->cfg.n_q_heads, k_per_seq, k_max, cache->max_seq_len, unit, sc,
+                                               idx, count, threshold, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HASHATTN_OK : hip_fail(ctx, e, "score_topk");
+}
+
+hashattn_status hashattn_gather_attend(hashattn_ctx* ctx, const void* q, const hashattn_kv* cache, const int32_t* idx,
+                                       const int32_t* count, int32_t batch, int32_t k_max, float scale, void* out,
+                                       void* stream)
+{
+    if (!ctx) return HASHATTN_INVALID_ARG;
+    if (hashattn_status s = check_cache(ctx, cache, batch, false, "gather_attend")) return s;
+    if (!q || !idx || !count || !out) return fail(ctx, HASHATTN_INVALID_ARG, "gather_attend: q, idx, count or out is NULL");
+    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(idx, 4) || !aligned(count, 4))
+        return fail(ctx, HASHATTN_INVALID_ARG, "gather_attend: q/out need 16-byte, idx/count 4-byte alignment");
+    if (k_max < 1) return fail(ctx, HASHATTN_INVALID_ARG, "gather_attend: k_max %d < 1", k_max);
+    if (k_max > ctx->cfg.max_k) return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "gather_attend: k_max %d exceeds max_k %lld", k_max, (long long)ctx->cfg.max_k);
+    if (!(scale == scale)) return fail(ctx, HASHATTN_INVALID_ARG, "gather_attend: scale is NaN");
+    int chunk, n_splits;
+    pick_splits(ctx, (int64_t)batch * ctx->cfg.n_q_heads, k_max, batch, &chunk, &n_splits);
+    const hipError_t e = ha::launch_gather_attend(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group,
+                                                  static_cast<const uint16_t*>(q), idx, count, batch, ctx->cfg.n_q_heads,
+                                                  k_max, chunk, n_splits, scale, ctx->part, static_cast<uint16_t*>(out),
+                                                  static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HASHATTN_OK : hip_fail(ctx, e, "gather_attend");
+}
+
+hashattn_status hashattn_dense_attend(hashattn_ctx* ctx, const void* q, const hashattn_kv* cache, int32_t batch,
+                                      float scale, void* out, void* stream)
+{
+    if (!ctx) return HASHATTN_INVALID_ARG;
+    if (hashattn_status s = check_cache(ctx, cache, batch, false, "dense_attend")) return s;
+    if (!q || !out) return fail(ctx, HASHATTN_INVALID_ARG, "dense_attend: q or out is NULL");
+    if (!aligned(q, 16) || !aligned(out, 16)) return fail(ctx, HASHATTN_INVALID_ARG, "dense_attend: q/out need 16-byte alignment");
+    if (!(scale == scale)) return fail(ctx, HASHATTN_INVALID_ARG, "dense_attend: scale is NaN");
+    int chunk, n_splits;
+    const int64_t total = cache->max_seq_len > 0 ? cache->max_seq_len : 1;
+    pick_splits(ctx, (int64_t)batch * ctx->cfg.n_kv_heads, total, batch, &chunk, &n_splits);
+    const hipError_t e = ha::launch_dense_attend(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group,
+                                                 static_cast<const uint16_t*>(q), batch, ctx->cfg.n_q_heads,
+                                                 cache->max_seq_len, chunk, n_splits, scale, ctx->part,
+                                                 static_cast<uint16_t*>(out), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HASHATTN_OK : hip_fail(ctx, e, "dense_attend");
+}
+
+}  // extern "C"

@@ -1,0 +1,290 @@
+// GATHER-ATT (section 4) and dense single-query SDPA (section 3.1) for gfx950.
+//
+// Both are split-K flash-decode kernels: the token list of one (sequence, head)
+// is cut into splits; a block keeps an online-softmax state (running max m,
+// running sum l, fp32 accumulator) per 16-lane row group, merges its 16 states
+// through LDS and writes one partial (acc[128], m, l); a second small kernel
+// merges the partials and rounds to bf16.
+//
+// A K or V row is 128 bf16 = 256 bytes = 16 lanes x 16 bytes, so one wave load
+// instruction fetches four rows; the <q, k> reduction runs inside a 16-lane DPP
+// row.  Each row group works on 4 rows at a time, so a block has 64 K rows and
+// 64 V rows (32 KiB) in flight per iteration.  The work is HBM bound (about one
+// flop per byte), so there is no MFMA here.  Logits are kept in log2 units
+// (scale * log2(e) folded into q) so that exp2 is the only transcendental.
+#include "kernels.hpp"
+
+#include <math.h>
+
+namespace ha {
+
+namespace {
+
+constexpr int kRowsPerIter = 64;   // rows a block consumes per loop iteration
+constexpr int kSlots = 16;         // row groups per block (4 waves x 4 groups)
+constexpr float kNegInf = -INFINITY;
+
+__device__ __forceinline__ uint4 load_row16(const uint16_t* base, int64_t row, int sub)
+{
+    return *reinterpret_cast<const uint4*>(base + row * kHeadDim + sub * 8);
+}
+
+// Merge the 16 per-group states of a block and write its partial.
+// st: [kSlots][kPartStride] floats in LDS, already filled and synchronised.
+__device__ __forceinline__ void write_partial(const float* st, float* part)
+{
+    const int tid = threadIdx.x;
+    if (tid < kHeadDim + 2) {
+        float M = kNegInf;
+#pragma unroll
+        for (int s = 0; s < kSlots; ++s) M = fmaxf(M, st[s * kPartStride + kHeadDim]);
+        const float Ms = (M == kNegInf) ? 0.f : M;
+        float sum = 0.f;
+        const int col = tid < kHeadDim ? tid : kHeadDim + 1;      // channel, or the l column
+#pragma unroll
+        for (int s = 0; s < kSlots; ++s)
+            sum += st[s * kPartStride + col] * exp2f(st[s * kPartStride + kHeadDim] - Ms);
+        if (tid < kHeadDim) part[tid] = sum;
+        else if (tid == kHeadDim) part[kHeadDim] = M;
+        else part[kHeadDim + 1] = sum;
+    }
+}
+
+template <bool PAGED>
+__global__ __launch_bounds__(256) void gather_attend_kernel(KvView c, const uint16_t* __restrict__ q,
+                                                            const int32_t* __restrict__ idx,
+                                                            const int32_t* __restrict__ count,
+                                                            int n_q_heads, int group, int k_max, int chunk,
+                                                            int n_splits, float scale_log2e,
+                                                            float* __restrict__ part)
+{
+    __shared__ float st[kSlots * kPartStride];
+    const int tid = threadIdx.x, lane = tid & 63, sub = lane & 15;
+    const int slot = tid >> 4;                       // 0..15
+    const int split = blockIdx.x, hq = blockIdx.y, b = blockIdx.z, kvh = hq / group;
+    const int64_t bh = (int64_t)b * n_q_heads + hq;
+    const int cnt = min(count[bh], k_max);
+    const int begin = split * chunk;
+    if (begin >= cnt) return;                        // the merge kernel skips unused splits
+    const int end = min(begin + chunk, cnt);
+    const int32_t* my_idx = idx + bh * k_max;
+
+    float qf[8];
+    unpack8(*reinterpret_cast<const uint4*>(q + bh * kHeadDim + sub * 8), qf);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) qf[i] *= scale_log2e;
+
+    float m = kNegInf, l = 0.f, acc[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc[i] = 0.f;
+
+    for (int base = begin; base < end; base += kRowsPerIter) {
+        uint4 kr[4], vr[4];
+        bool ok[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = base + i * kSlots + slot;
+            ok[i] = r < end;
+            const int tok = my_idx[ok[i] ? r : end - 1];
+            const int64_t row = row_of<PAGED>(c, b, kvh, tok);
+            kr[i] = load_row16(c.k, row, sub);
+            vr[i] = load_row16(c.v, row, sub);
+        }
+        float x[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float kf[8];
+            unpack8(kr[i], kf);
+            float d = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) d = fmaf(qf[e], kf[e], d);
+            d = row16_sum(d);
+            x[i] = ok[i] ? d : kNegInf;
+        }
+        const float m_new = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), m);
+        const float ref = (m_new == kNegInf) ? 0.f : m_new;      // a group may have seen no valid row yet
+        const float alpha = exp2f(m - ref);
+        float p[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) p[i] = exp2f(x[i] - ref);
+        l = l * alpha + (p[0] + p[1]) + (p[2] + p[3]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] *= alpha;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float vf[8];
+            unpack8(vr[i], vf);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[e] = fmaf(p[i], vf[e], acc[e]);
+        }
+        m = m_new;
+    }
+
+    // a group that saw no valid row keeps m = -inf, l = 0 (possible when end - begin < 16)
+    float* mine = st + slot * kPartStride;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) mine[sub * 8 + e] = acc[e];
+    if (sub == 0) { mine[kHeadDim] = m; mine[kHeadDim + 1] = l; }
+    __syncthreads();
+    write_partial(st, part + (bh * n_splits + split) * kPartStride);
+}
+
+// Dense decode: the block walks a contiguous token range of one KV head and serves
+// the G query heads of the group from one read of every K/V row.
+template <int G, bool PAGED>
+__global__ __launch_bounds__(256) void dense_attend_kernel(KvView c, const uint16_t* __restrict__ q,
+                                                           int n_q_heads, int n_cap, int chunk, int n_splits,
+                                                           float scale_log2e, float* __restrict__ part)
+{
+    __shared__ float st[kSlots * kPartStride];
+    const int tid = threadIdx.x, lane = tid & 63, sub = lane & 15;
+    const int slot = tid >> 4;
+    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int n = min(c.seq_lens[b], n_cap);
+    const int begin = split * chunk;
+    if (begin >= n) return;
+    const int end = min(begin + chunk, n);
+
+    float qf[G][8], acc[G][8], m[G], l[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        const int64_t bh = (int64_t)b * n_q_heads + kvh * G + j;
+        unpack8(*reinterpret_cast<const uint4*>(q + bh * kHeadDim + sub * 8), qf[j]);
+        m[j] = kNegInf;
+        l[j] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) { qf[j][e] *= scale_log2e; acc[j][e] = 0.f; }
+    }
+
+    for (int base = begin; base < end; base += kRowsPerIter) {
+        uint4 kr[4], vr[4];
+        bool ok[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int t = base + i * kSlots + slot;
+            ok[i] = t < end;
+            const int64_t row = row_of<PAGED>(c, b, kvh, ok[i] ? t : end - 1);
+            kr[i] = load_row16(c.k, row, sub);
+            vr[i] = load_row16(c.v, row, sub);
+        }
+        float kf[4][8], vf[4][8];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { unpack8(kr[i], kf[i]); unpack8(vr[i], vf[i]); }
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            float x[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float d = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) d = fmaf(qf[j][e], kf[i][e], d);
+                d = row16_sum(d);
+                x[i] = ok[i] ? d : kNegInf;
+            }
+            const float m_new = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), m[j]);
+            const float ref = (m_new == kNegInf) ? 0.f : m_new;
+            const float alpha = exp2f(m[j] - ref);
+            float p[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) p[i] = exp2f(x[i] - ref);
+            l[j] = l[j] * alpha + (p[0] + p[1]) + (p[2] + p[3]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[j][e] *= alpha;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p[i], vf[i][e], acc[j][e]);
+            m[j] = m_new;
+        }
+    }
+
+    float* mine = st + slot * kPartStride;
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        if (j > 0) __syncthreads();                  // st is reused head after head
+#pragma unroll
+        for (int e = 0; e < 8; ++e) mine[sub * 8 + e] = acc[j][e];
+        if (sub == 0) { mine[kHeadDim] = m[j]; mine[kHeadDim + 1] = l[j]; }
+        __syncthreads();
+        const int64_t bh = (int64_t)b * n_q_heads + kvh * G + j;
+        write_partial(st, part + (bh * n_splits + split) * kPartStride);
+    }
+}
+
+// Merge split partials of one (sequence, query head): out = sum_s acc_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
+// lens: per head (count, PER_HEAD) or per sequence (seq_lens); splits beyond ceil(len / chunk) were not written.
+template <bool PER_HEAD>
+__global__ __launch_bounds__(128) void merge_partials_kernel(const float* __restrict__ part,
+                                                             const int32_t* __restrict__ lens, int len_cap,
+                                                             int n_q_heads, int chunk, int n_splits,
+                                                             uint16_t* __restrict__ out)
+{
+    const int hq = blockIdx.x, b = blockIdx.y, ch = threadIdx.x;
+    const int64_t bh = (int64_t)b * n_q_heads + hq;
+    const int len = min(PER_HEAD ? lens[bh] : lens[b], len_cap);
+    const int used = min(n_splits, (len + chunk - 1) / chunk);
+    const float* p = part + bh * n_splits * kPartStride;
+    float M = kNegInf;
+    for (int s = 0; s < used; ++s) M = fmaxf(M, p[s * kPartStride + kHeadDim]);
+    float num = 0.f, den = 0.f;
+    for (int s = 0; s < used; ++s) {
+        const float w = exp2f(p[s * kPartStride + kHeadDim] - M);
+        num = fmaf(p[s * kPartStride + ch], w, num);
+        den = fmaf(p[s * kPartStride + kHeadDim + 1], w, den);
+    }
+    const float o = (used > 0 && den > 0.f) ? num / den : 0.f;
+    out[bh * kHeadDim + ch] = (uint16_t)f32_to_bf16(o);
+}
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+}  // namespace
+
+hipError_t launch_gather_attend(const KvView& kv, bool paged, int group, const uint16_t* q,
+                                const int32_t* idx, const int32_t* count, int batch, int n_q_heads,
+                                int k_max, int chunk, int n_splits, float scale, float* part,
+                                uint16_t* out, hipStream_t stream)
+{
+    const dim3 grid(n_splits, n_q_heads, batch), block(256);
+    if (paged)
+        gather_attend_kernel<true><<<grid, block, 0, stream>>>(kv, q, idx, count, n_q_heads, group, k_max,
+                                                               chunk, n_splits, scale * kLog2e, part);
+    else
+        gather_attend_kernel<false><<<grid, block, 0, stream>>>(kv, q, idx, count, n_q_heads, group, k_max,
+                                                                chunk, n_splits, scale * kLog2e, part);
+    merge_partials_kernel<true><<<dim3(n_q_heads, batch), 128, 0, stream>>>(part, count, k_max, n_q_heads,
+                                                                            chunk, n_splits, out);
+    return hipGetLastError();
+}
+
+template <int G>
+static void launch_dense_g(const KvView& kv, bool paged, const uint16_t* q, int batch, int n_q_heads,
+                           int max_seq_len, int chunk, int n_splits, float scale, float* part,
+                           hipStream_t stream)
+{
+    const dim3 grid(n_splits, kv.n_kv_heads, batch), block(256);
+    if (paged)
+        dense_attend_kernel<G, true><<<grid, block, 0, stream>>>(kv, q, n_q_heads, max_seq_len, chunk,
+                                                                 n_splits, scale * kLog2e, part);
+    else
+        dense_attend_kernel<G, false><<<grid, block, 0, stream>>>(kv, q, n_q_heads, max_seq_len, chunk,
+                                                                  n_splits, scale * kLog2e, part);
+}
+
+hipError_t launch_dense_attend(const KvView& kv, bool paged, int group, const uint16_t* q,
+                               int batch, int n_q_heads, int max_seq_len, int chunk, int n_splits,
+                               float scale, float* part, uint16_t* out, hipStream_t stream)
+{
+    switch (group) {
+    case 1: launch_dense_g<1>(kv, paged, q, batch, n_q_heads, max_seq_len, chunk, n_splits, scale, part, stream); break;
+    case 2: launch_dense_g<2>(kv, paged, q, batch, n_q_heads, max_seq_len, chunk, n_splits, scale, part, stream); break;
+    case 4: launch_dense_g<4>(kv, paged, q, batch, n_q_heads, max_seq_len, chunk, n_splits, scale, part, stream); break;
+    case 8: launch_dense_g<8>(kv, paged, q, batch, n_q_heads, max_seq_len, chunk, n_splits, scale, part, stream); break;
+    default: return hipErrorInvalidValue;
+    }
+    merge_partials_kernel<false><<<dim3(n_q_heads, batch), 128, 0, stream>>>(part, kv.seq_lens, max_seq_len,
+                                                                             n_q_heads, chunk, n_splits, out);
+    return hipGetLastError();
+}
+
+}  // namespace ha

@@ -1,0 +1,90 @@
+// Device-side helpers shared by the HashAttention kernels (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ha {
+
+constexpr int kHeadDim = 128;     // bf16 elements per K/V row (256 bytes)
+constexpr int kBits = 32;         // signature width
+constexpr int kBins = 33;         // Hamming similarity takes values 0..32
+constexpr int kPage = 16;         // tokens per page in the paged layout
+constexpr int kWave = 64;
+constexpr int kPartStride = 132;  // floats per split partial: acc[128], m, l, pad
+
+// Plain view of the caller's KV cache, passed to kernels by value.
+struct KvView {
+    const uint16_t* k;
+    const uint16_t* v;
+    uint32_t* codes;
+    const int32_t* page_table;
+    int32_t* seq_lens;
+    int64_t n_max;
+    int32_t max_pages_per_seq;
+    int32_t n_kv_heads;
+};
+
+// Row index (in rows) of token t of sequence b, KV head h.
+template <bool PAGED>
+__device__ __forceinline__ int64_t row_of(const KvView& c, int b, int h, int t)
+{
+    if constexpr (PAGED) {
+        const int64_t page = c.page_table[(int64_t)b * c.max_pages_per_seq + (t >> 4)];
+        return (page * c.n_kv_heads + h) * kPage + (t & (kPage - 1));
+    } else {
+        return ((int64_t)b * c.n_kv_heads + h) * c.n_max + t;
+    }
+}
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+
+// fp32 -> bf16 bits, round to nearest even (inputs are finite here).
+__device__ __forceinline__ uint32_t f32_to_bf16(float f)
+{
+    const uint32_t u = __float_as_uint(f);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Unpack 8 bf16 (one 16-byte load) to fp32.
+__device__ __forceinline__ void unpack8(const uint4& r, float (&f)[8])
+{
+    f[0] = bf16_lo(r.x); f[1] = bf16_hi(r.x);
+    f[2] = bf16_lo(r.y); f[3] = bf16_hi(r.y);
+    f[4] = bf16_lo(r.z); f[5] = bf16_hi(r.z);
+    f[6] = bf16_lo(r.w); f[7] = bf16_hi(r.w);
+}
+
+// DPP rotate inside a 16-lane row (no LDS traffic).
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the 16 lanes of a DPP row; every lane of the row gets the total.
+__device__ __forceinline__ float row16_sum(float x)
+{
+    x += dpp_f<0x128>(x);   // row_ror:8
+    x += dpp_f<0x124>(x);   // row_ror:4
+    x += dpp_f<0x122>(x);   // row_ror:2
+    x += dpp_f<0x121>(x);   // row_ror:1
+    return x;
+}
+
+__device__ __forceinline__ int wave_sum_i32(int x)
+{
+    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
+    return x;
+}
+
+// Number of set bits of a wave mask in lanes below the calling lane.
+__device__ __forceinline__ int lanes_below(uint64_t mask)
+{
+    return (int)__builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                          __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+__device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+}  // namespace ha

@@ -1,0 +1,303 @@
+// Mapping functions phi_q and phi_kv (section 4.1, eq. 2) for gfx950:
+//   code = pack_j [ F(x)_j > 0 ],  F = small MLP with SiLU between layers, fp32.
+//
+// Two kernels:
+//   encode_vec   few vectors per head (the decode step: one query per head, one
+//                appended key per KV head).  GEMV shaped: a block owns one head
+//                and up to 8 vectors, each weight is read once per block and
+//                applied to all of them.
+//   encode_bulk  many tokens per head (building the key-code store after
+//                prefill).  A block owns a tile of 64 tokens of one KV head; the
+//                activations sit in LDS, every thread keeps an (R x 8) register
+//                tile of outputs and streams the weights from L2.
+// Weights are fp32 and the accumulation is fp32, so a bit can differ from an
+// fp64 evaluation only where the pre-sign activation is within rounding of 0.
+#include "kernels.hpp"
+
+namespace ha {
+
+namespace {
+
+constexpr int kMaxWidth = 256;
+constexpr int kVecPerBlock = 8;
+constexpr int kTile = 64;
+
+__device__ __forceinline__ float silu(float z) { return z / (1.f + expf(-z)); }
+
+// ---------------------------------------------------------------- encode_vec
+// act: [2][kVecPerBlock][kMaxWidth] floats; r: kVecPerBlock * 256 floats of partial sums, indexed
+// [part][vec][j] with parts * dout = 256.  On return act[cur] holds the pre-sign activations of the
+// last layer; returns cur.
+__device__ int mlp_gemv(const MlpView& phi, int head, float (*act)[kVecPerBlock][kMaxWidth], float* r)
+{
+    const int tid = threadIdx.x;
+    int cur = 0;
+    for (int l = 0; l < phi.n_layers; ++l) {
+        const int di = phi.dims[l], dout = phi.dims[l + 1];
+        const int parts = 256 / dout;
+        const int j = tid % dout, p = tid / dout;
+        const int span = di / parts;
+        const float* W = phi.W[l] + (int64_t)head * di * dout;
+        float acc[kVecPerBlock];
+#pragma unroll
+        for (int v = 0; v < kVecPerBlock; ++v) acc[v] = 0.f;
+        for (int i = p * span; i < (p + 1) * span; ++i) {
+            const float w = W[(int64_t)i * dout + j];
+#pragma unroll
+            for (int v = 0; v < kVecPerBlock; ++v) acc[v] = fmaf(act[cur][v][i], w, acc[v]);
+        }
+#pragma unroll
+        for (int v = 0; v < kVecPerBlock; ++v) r[(p * kVecPerBlock + v) * dout + j] = acc[v];
+        __syncthreads();
+        const bool last = (l + 1 == phi.n_layers);
+        for (int o = tid; o < kVecPerBlock * dout; o += 256) {
+            const int v = o / dout, jj = o - v * dout;
+            float z = 0.f;
+            for (int pp = 0; pp < parts; ++pp) z += r[(pp * kVecPerBlock + v) * dout + jj];
+            if (phi.bias[l]) z += phi.bias[l][(int64_t)head * dout + jj];
+            act[cur ^ 1][v][jj] = last ? z : silu(z);
+        }
+        __syncthreads();
+        cur ^= 1;
+    }
+    return cur;
+}
+
+// MODE 0: queries.  x = q [B][H][128]; codes -> q_codes [B][H]; vector index = b.
+// MODE 1: appended keys.  x = k_new [B][H][n_new][128]; vector index = b * n_new + j; the K and V rows
+//         are copied to cache position seq_lens[b] + j and the code stored there.
+template <int MODE, bool PAGED>
+__global__ __launch_bounds__(256) void encode_vec_kernel(MlpView phi, int n_heads, const uint16_t* __restrict__ x,
+                                                         const uint16_t* __restrict__ v_new, int n_vec, int n_new,
+                                                         uint32_t* __restrict__ q_codes, KvView c, int n_cap)
+{
+    __shared__ float act[2][kVecPerBlock][kMaxWidth];
+    __shared__ float red[kVecPerBlock * 256];
+    const int tid = threadIdx.x;
+    const int head = blockIdx.x, v0 = blockIdx.y * kVecPerBlock;
+    const int d = phi.dims[0];                                     // 128
+
+    for (int o = tid; o < kVecPerBlock * d; o += 256) {
+        const int v = o / d, i = o - v * d, vec = v0 + v;
+        float val = 0.f;
+        if (vec < n_vec) {
+            const int b = MODE == 0 ? vec : vec / n_new, jn = MODE == 0 ? 0 : vec - b * n_new;
+            const int64_t src = MODE == 0 ? ((int64_t)b * n_heads + head)
+                                          : (((int64_t)b * n_heads + head) * n_new + jn);
+            val = __uint_as_float((uint32_t)x[src * d + i] << 16);
+        }
+        act[0][v][i] = val;
+    }
+    __syncthreads();
+    const int cur = mlp_gemv(phi, head, act, red);
+
+    // thread (v = tid / 32, j = tid % 32) owns bit j of vector v; a wave ballot packs two vectors
+    const int v = tid >> 5, j = tid & 31, vec = v0 + v;
+    const uint64_t mask = __ballot(act[cur][v][j] > 0.f);
+    const uint32_t code = (uint32_t)((tid & 32) ? (mask >> 32) : mask);
+    if (vec < n_vec) {
+        const int b = MODE == 0 ? vec : vec / n_new, jn = MODE == 0 ? 0 : vec - b * n_new;
+        if constexpr (MODE == 0) {
+            if (j == 0) q_codes[(int64_t)b * n_heads + head] = code;
+        } else {
+            const int64_t row = row_of<PAGED>(c, b, head, min(c.seq_lens[b], n_cap) + jn);
+            const int64_t src = ((int64_t)b * n_heads + head) * n_new + jn;
+            if (j == 0) c.codes[row] = code;
+            // 32 threads copy the 256-byte K row and V row, 16 bytes each (16 + 16 threads)
+            const uint4* from = reinterpret_cast<const uint4*>((j < 16 ? x : v_new) + src * kHeadDim) + (j & 15);
+            uint4* to = reinterpret_cast<uint4*>(const_cast<uint16_t*>(j < 16 ? c.k : c.v) + row * kHeadDim) + (j & 15);
+            *to = *from;
+        }
+    }
+}
+
+__global__ void bump_seq_lens_kernel(int32_t* seq_lens, int batch, int n_new)
+{
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b < batch) seq_lens[b] += n_new;
+}
+
+// ---------------------------------------------------------------- encode_bulk
+// One layer on a 64-token tile: out[t][o] = sum_i in[t][i] W[i][o] (+bias), SiLU unless last.
+// Thread (ty, tx): outputs tx*8 .. tx*8+7 of tokens ty + rows*r, r < R.
+template <int DOUT>
+__device__ __forceinline__ void bulk_layer(const float* __restrict__ W, const float* __restrict__ bias, int di,
+                                           const float* in, int in_pitch, float* out, int out_pitch, bool last)
+{
+    constexpr int NOT = DOUT / 8, ROWS = 256 / NOT, R = kTile / ROWS;
+    const int tx = threadIdx.x % NOT, ty = threadIdx.x / NOT;
+    float acc[R][8];
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[r][e] = 0.f;
+    for (int i = 0; i < di; ++i) {
+        const float4 w0 = *reinterpret_cast<const float4*>(W + (int64_t)i * DOUT + tx * 8);
+        const float4 w1 = *reinterpret_cast<const float4*>(W + (int64_t)i * DOUT + tx * 8 + 4);
+        const float w[8] = {w0.x, w0.y, w0.z, w0.w, w1.x, w1.y, w1.z, w1.w};
+#pragma unroll
+        for (int r = 0; r < R; ++r) {
+            const float xv = in[(ty + ROWS * r) * in_pitch + i];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[r][e] = fmaf(xv, w[e], acc[r][e]);
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < R; ++r)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            float z = acc[r][e];
+            if (bias) z += bias[tx * 8 + e];
+            out[(ty + ROWS * r) * out_pitch + tx * 8 + e] = last ? z : silu(z);
+        }
+}
+
+__device__ __forceinline__ void bulk_layer_any(int dout, const float* W, const float* bias, int di,
+                                               const float* in, int in_pitch, float* out, int out_pitch, bool last)
+{
+    switch (dout) {
+    case 32:  bulk_layer<32>(W, bias, di, in, in_pitch, out, out_pitch, last); break;
+    case 64:  bulk_layer<64>(W, bias, di, in, in_pitch, out, out_pitch, last); break;
+    case 128: bulk_layer<128>(W, bias, di, in, in_pitch, out, out_pitch, last); break;
+    default:  bulk_layer<256>(W, bias, di, in, in_pitch, out, out_pitch, last); break;
+    }
+}
+
+// Encodes, for every sequence, the cached key rows of tokens [start_b, start_b + cnt_b):
+//   from_end = 1: the last min(n_new, len) tokens (in-place rebuild)
+//   from_end = 0: the n_new tokens starting at len (rows just appended, seq_lens not yet bumped)
+template <bool PAGED>
+__global__ __launch_bounds__(256) void encode_bulk_kernel(MlpView phi, KvView c, int n_cap, int64_t n_new, int from_end)
+{
+    extern __shared__ float lds[];                         // 2 x kTile x P floats
+    int widest = phi.dims[0];
+    for (int l = 1; l <= phi.n_layers; ++l) widest = max(widest, phi.dims[l]);
+    const int P = widest + 1;                              // LDS pitch, odd to spread banks
+    float* bufA = lds;
+    float* bufB = lds + kTile * P;
+    const int tid = threadIdx.x;
+    const int head = blockIdx.y, b = blockIdx.z;
+    const int len = min(c.seq_lens[b], n_cap);
+    const int64_t start = from_end ? (len > n_new ? len - n_new : 0) : len;
+    const int64_t cnt = from_end ? len - start : n_new;
+    const int64_t t0 = (int64_t)blockIdx.x * kTile;
+    if (t0 >= cnt) return;
+    const int n_tok = (int)min((int64_t)kTile, cnt - t0);
+
+    // load the key tile as fp32: 16 lanes x 16 bytes per row
+    for (int o = tid; o < kTile * 16; o += 256) {
+        const int t = o >> 4, sub = o & 15;
+        float f[8];
+        if (t < n_tok) {
+            const int64_t row = row_of<PAGED>(c, b, head, (int)(start + t0 + t));
+            unpack8(*reinterpret_cast<const uint4*>(c.k + row * kHeadDim + sub * 8), f);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) f[e] = 0.f;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) bufA[t * P + sub * 8 + e] = f[e];
+    }
+    __syncthreads();
+
+    float* in = bufA;
+    float* out = bufB;
+    for (int l = 0; l < phi.n_layers; ++l) {
+        const int di = phi.dims[l], dout = phi.dims[l + 1];
+        const float* W = phi.W[l] + (int64_t)head * di * dout;
+        const float* bias = phi.bias[l] ? phi.bias[l] + (int64_t)head * dout : nullptr;
+        bulk_layer_any(dout, W, bias, di, in, P, out, P, l + 1 == phi.n_layers);
+        __syncthreads();
+        float* t = in; in = out; out = t;
+    }
+    if (tid < n_tok) {
+        uint32_t code = 0u;
+#pragma unroll
+        for (int j = 0; j < kBits; ++j) code |= (in[tid * P + j] > 0.f ? 1u : 0u) << j;
+        c.codes[row_of<PAGED>(c, b, head, (int)(start + t0 + tid))] = code;
+    }
+}
+
+// Copies appended rows k_new/v_new [B][H][n_new][128] into the cache at positions len_b + j.
+template <bool PAGED>
+__global__ __launch_bounds__(256) void append_rows_kernel(KvView c, const uint16_t* __restrict__ k_new,
+                                                          const uint16_t* __restrict__ v_new, int64_t n_new, int n_cap)
+{
+    const int head = blockIdx.y, b = blockIdx.z;
+    const int64_t o = (int64_t)blockIdx.x * 256 + threadIdx.x;     // 16-byte piece index inside (b, head)
+    const int64_t j = o >> 4;
+    const int sub = (int)(o & 15);
+    if (j >= n_new) return;
+    const int64_t src = (((int64_t)b * c.n_kv_heads + head) * n_new + j) * kHeadDim + sub * 8;
+    const int64_t row = row_of<PAGED>(c, b, head, (int)(min(c.seq_lens[b], n_cap) + j));
+    *reinterpret_cast<uint4*>(const_cast<uint16_t*>(c.k) + row * kHeadDim + sub * 8) =
+        *reinterpret_cast<const uint4*>(k_new + src);
+    *reinterpret_cast<uint4*>(const_cast<uint16_t*>(c.v) + row * kHeadDim + sub * 8) =
+        *reinterpret_cast<const uint4*>(v_new + src);
+}
+
+// LDS bytes of encode_bulk for this network; raises the kernel's dynamic LDS limit when it passes 64 KiB.
+hipError_t bulk_lds_setup(const MlpView& phi, bool paged, size_t* bytes)
+{
+    int widest = phi.dims[0];
+    for (int l = 1; l <= phi.n_layers; ++l) widest = widest > phi.dims[l] ? widest : phi.dims[l];
+    *bytes = sizeof(float) * 2 * kTile * (size_t)(widest + 1);
+    const void* fn = paged ? reinterpret_cast<const void*>(&encode_bulk_kernel<true>)
+                           : reinterpret_cast<const void*>(&encode_bulk_kernel<false>);
+    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)*bytes);
+}
+
+}  // namespace
+
+hipError_t launch_encode_query(const MlpView& phi, const uint16_t* q, int batch, int n_heads,
+                               uint32_t* q_codes, hipStream_t stream)
+{
+    const dim3 grid(n_heads, (batch + kVecPerBlock - 1) / kVecPerBlock);
+    KvView none{};
+    encode_vec_kernel<0, false><<<grid, 256, 0, stream>>>(phi, n_heads, q, nullptr, batch, 1, q_codes, none, 0);
+    return hipGetLastError();
+}
+
+hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
+                              const uint16_t* k_new, const uint16_t* v_new,
+                              int batch, int64_t n_new, int max_seq_len, hipStream_t stream)
+{
+    const int H = kv.n_kv_heads;
+    size_t lds_bytes = 0;
+    if (k_new) {
+        if (n_new * batch <= 4 * kVecPerBlock) {
+            // decode-time append: one GEMV-shaped launch writes rows and codes
+            const int n_vec = (int)(batch * n_new);
+            const dim3 grid(H, (n_vec + kVecPerBlock - 1) / kVecPerBlock);
+            if (paged)
+                encode_vec_kernel<1, true><<<grid, 256, 0, stream>>>(phi, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len);
+            else
+                encode_vec_kernel<1, false><<<grid, 256, 0, stream>>>(phi, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len);
+        } else {
+            const dim3 cgrid((unsigned)((n_new * 16 + 255) / 256), H, batch);
+            const dim3 egrid((unsigned)((n_new + kTile - 1) / kTile), H, batch);
+            if (hipError_t e = bulk_lds_setup(phi, paged, &lds_bytes); e != hipSuccess) return e;
+            if (paged) {
+                append_rows_kernel<true><<<cgrid, 256, 0, stream>>>(kv, k_new, v_new, n_new, max_seq_len);
+                encode_bulk_kernel<true><<<egrid, 256, lds_bytes, stream>>>(phi, kv, max_seq_len, n_new, 0);
+            } else {
+                append_rows_kernel<false><<<cgrid, 256, 0, stream>>>(kv, k_new, v_new, n_new, max_seq_len);
+                encode_bulk_kernel<false><<<egrid, 256, lds_bytes, stream>>>(phi, kv, max_seq_len, n_new, 0);
+            }
+        }
+        bump_seq_lens_kernel<<<(batch + 255) / 256, 256, 0, stream>>>(kv.seq_lens, batch, (int)n_new);
+    } else {
+        const int64_t span = n_new < max_seq_len ? n_new : max_seq_len;
+        if (span > 0) {
+            const dim3 egrid((unsigned)((span + kTile - 1) / kTile), H, batch);
+            if (hipError_t e = bulk_lds_setup(phi, paged, &lds_bytes); e != hipSuccess) return e;
+            if (paged)
+                encode_bulk_kernel<true><<<egrid, 256, lds_bytes, stream>>>(phi, kv, max_seq_len, n_new, 1);
+            else
+                encode_bulk_kernel<false><<<egrid, 256, lds_bytes, stream>>>(phi, kv, max_seq_len, n_new, 1);
+        }
+    }
+    return hipGetLastError();
+}
+
+}  // namespace ha

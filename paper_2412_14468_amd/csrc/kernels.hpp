@@ -1,0 +1,44 @@
+// Host-side launchers of the HashAttention kernels.  Each launcher assumes its
+// arguments were validated by the C ABI layer and enqueues on `stream`.
+#pragma once
+#include "common.hpp"
+
+namespace ha {
+
+// Mapping network on the device side (weights are caller-owned device memory).
+struct MlpView {
+    int32_t n_layers;
+    int32_t dims[5];
+    const float* W[4];
+    const float* bias[4];
+};
+
+struct TopkScratch {
+    uint16_t* unit_hist;   // [B][Hq][33][units_pitch]
+    int2* unit_off;        // [B][Hq][units_pitch]: {output offset, tie quota inside the unit}
+    int2* sel;             // [B][Hq]: {threshold T, unused}
+    int32_t units_pitch;
+};
+
+hipError_t launch_encode_query(const MlpView& phi, const uint16_t* q, int batch, int n_heads,
+                               uint32_t* q_codes, hipStream_t stream);
+
+hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
+                              const uint16_t* k_new, const uint16_t* v_new,
+                              int batch, int64_t n_new, int max_seq_len, hipStream_t stream);
+
+hipError_t launch_score_topk(const KvView& kv, bool paged, int group, const uint32_t* q_codes,
+                             int batch, int n_q_heads, const int32_t* k_per_seq, int k_max,
+                             int max_seq_len, int unit_tokens, const TopkScratch& sc,
+                             int32_t* idx, int32_t* count, uint8_t* threshold, hipStream_t stream);
+
+hipError_t launch_gather_attend(const KvView& kv, bool paged, int group, const uint16_t* q,
+                                const int32_t* idx, const int32_t* count, int batch, int n_q_heads,
+                                int k_max, int chunk, int n_splits, float scale, float* part,
+                                uint16_t* out, hipStream_t stream);
+
+hipError_t launch_dense_attend(const KvView& kv, bool paged, int group, const uint16_t* q,
+                               int batch, int n_q_heads, int max_seq_len, int chunk, int n_splits,
+                               float scale, float* part, uint16_t* out, hipStream_t stream);
+
+}  // namespace ha
