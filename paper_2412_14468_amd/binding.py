@@ -53,6 +53,9 @@ def load() -> C.CDLL:
         raise ImportError(
             f"{LIB_PATH} is missing: build it with `python -m paper_2412_14468_amd.build` "
             "(hipcc --offload-arch=gfx950); the HashAttention path has no CPU fallback")
+    # torch goes first: its HIP runtime must be the one this process uses (device memory and streams
+    # come from torch), and the library must bind to that same runtime rather than load a second one
+    import torch  # noqa: F401
     L = C.CDLL(LIB_PATH)
     vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
     L.hashattn_create.restype = i32
