@@ -128,7 +128,8 @@ int pick_unit_tokens(const hashattn_ctx* ctx, int batch, int max_seq_len)
     // aim for about 8192 waves in flight over the whole grid, never more units than the scratch pitch
     while (unit < kMaxUnit &&
            (lanes * ((max_seq_len + unit - 1) / unit) > 8192 ||
-            (max_seq_len + unit - 1) / unit > ctx->units_pitch))
+            (max_seq_len + unit - 1) / unit > ctx->units_pitch ||
+            (max_seq_len + unit - 1) / unit > ha::kMaxScanUnits))
         unit *= 2;
     return unit;
 }
@@ -176,8 +177,10 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
     if (cfg->page_size != 0 && cfg->page_size != ha::kPage)
         return fail(nullptr, HASHATTN_UNSUPPORTED, "create: page_size %d, only 0 (contiguous) or 16", cfg->page_size);
     if (cfg->max_batch < 1 || cfg->max_batch > 65535) return fail(nullptr, HASHATTN_INVALID_ARG, "create: max_batch %d not in 1..65535", cfg->max_batch);
-    if (cfg->max_context < 1 || cfg->max_context > (int64_t)1 << 30)
-        return fail(nullptr, HASHATTN_INVALID_ARG, "create: max_context %lld not in 1..2^30", (long long)cfg->max_context);
+    const int64_t context_limit = (int64_t)ha::kMaxScanUnits * kMaxUnit;       // 15.7 M tokens
+    if (cfg->max_context < 1 || cfg->max_context > context_limit)
+        return fail(nullptr, HASHATTN_INVALID_ARG, "create: max_context %lld not in 1..%lld", (long long)cfg->max_context,
+                    (long long)context_limit);
     if (cfg->max_k < 1 || cfg->max_k > (int64_t)1 << 30)
         return fail(nullptr, HASHATTN_INVALID_ARG, "create: max_k %lld not in 1..2^30", (long long)cfg->max_k);
     if (cfg->n_kv_heads > 65535) return fail(nullptr, HASHATTN_INVALID_ARG, "create: n_kv_heads too large");
@@ -196,6 +199,7 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
     const int64_t min_pitch = (cfg->max_context + kMaxUnit - 1) / kMaxUnit;
     const int64_t budget = (int64_t)(64 << 20) / (bh * ha::kBins * (int64_t)sizeof(uint16_t));   // 64 MiB of histograms
     if (pitch > budget) pitch = budget;
+    if (pitch > ha::kMaxScanUnits) pitch = ha::kMaxScanUnits;
     if (pitch < min_pitch) pitch = min_pitch;
     pitch = (pitch + 7) / 8 * 8;
     ctx->units_pitch = (int32_t)pitch;
@@ -215,7 +219,7 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
         (e = hipMalloc(reinterpret_cast<void**>(&ctx->sel), sel_bytes)) != hipSuccess ||
         (e = hipMalloc(reinterpret_cast<void**>(&ctx->part), part_bytes)) != hipSuccess) {
         hashattn_destroy(ctx);
-        return fail(nullptr, HASHATTN_HIP_ERROR, "create: hipMalloc of %lld scratch bytes: %s",
+        return fail(nullptr, HASHATTN_HIP_ERROR, "create: allocating %lld scratch bytes: %s",
                     (long long)ctx->scratch_bytes, hipGetErrorString(e));
     }
     *out = ctx;

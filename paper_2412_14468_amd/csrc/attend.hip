@@ -3,15 +3,19 @@
 // Both are split-K flash-decode kernels: the token list of one (sequence, head)
 // is cut into splits; a block keeps an online-softmax state (running max m,
 // running sum l, fp32 accumulator) per 16-lane row group, merges its 16 states
-// through LDS and writes one partial (acc[128], m, l); a second small kernel
-// merges the partials and rounds to bf16.
+// through LDS and writes one partial (acc[128], m, l).  A second, small kernel
+// merges the partials of a head and rounds to bf16.  (Merging in the block that
+// finishes last was measured and dropped: the device-scope release/acquire it
+// needs writes back and invalidates the XCD's whole L2 in every block, which
+// cost far more than the extra launch.)
 //
 // A K or V row is 128 bf16 = 256 bytes = 16 lanes x 16 bytes, so one wave load
 // instruction fetches four rows; the <q, k> reduction runs inside a 16-lane DPP
-// row.  Each row group works on 4 rows at a time, so a block has 64 K rows and
-// 64 V rows (32 KiB) in flight per iteration.  The work is HBM bound (about one
-// flop per byte), so there is no MFMA here.  Logits are kept in log2 units
-// (scale * log2(e) folded into q) so that exp2 is the only transcendental.
+// row.  Each row group works on 4 rows at a time and the loads of the next 64
+// rows are issued before the current 64 are consumed, so a block keeps up to
+// 64 KiB of rows in flight.  The work is HBM bound (about one flop per byte), so
+// there is no MFMA here.  Logits are kept in log2 units (scale * log2(e) folded
+// into q) so that exp2 is the only transcendental.
 #include "kernels.hpp"
 
 #include <math.h>
@@ -22,6 +26,7 @@ namespace {
 
 constexpr int kRowsPerIter = 64;   // rows a block consumes per loop iteration
 constexpr int kSlots = 16;         // row groups per block (4 waves x 4 groups)
+constexpr int kMaxSplits = 256;
 constexpr float kNegInf = -INFINITY;
 
 __device__ __forceinline__ uint4 load_row16(const uint16_t* base, int64_t row, int sub)
@@ -29,8 +34,41 @@ __device__ __forceinline__ uint4 load_row16(const uint16_t* base, int64_t row, i
     return *reinterpret_cast<const uint4*>(base + row * kHeadDim + sub * 8);
 }
 
-// Merge the 16 per-group states of a block and write its partial.
-// st: [kSlots][kPartStride] floats in LDS, already filled and synchronised.
+// Online-softmax update of one row group with 4 rows (logits x in log2 units, -inf = no row).
+__device__ __forceinline__ void absorb4(const float (&x)[4], const uint4 (&vr)[4], float& m, float& l,
+                                        float (&acc)[8])
+{
+    const float m_new = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), m);
+    const float ref = (m_new == kNegInf) ? 0.f : m_new;      // a group may have seen no valid row yet
+    const float alpha = exp2f(m - ref);
+    float p[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) p[i] = exp2f(x[i] - ref);
+    l = l * alpha + (p[0] + p[1]) + (p[2] + p[3]);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] *= alpha;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float vf[8];
+        unpack8(vr[i], vf);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[e] = fmaf(p[i], vf[e], acc[e]);
+    }
+    m = m_new;
+}
+
+__device__ __forceinline__ float dot8_row16(const float (&qf)[8], const uint4& kr)
+{
+    float kf[8];
+    unpack8(kr, kf);
+    float d = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) d = fmaf(qf[e], kf[e], d);
+    return row16_sum(d);
+}
+
+// Merge the 16 per-group states of a block (st: [kSlots][kPartStride] floats in LDS, already
+// filled and synchronised) and write the block's partial.
 __device__ __forceinline__ void write_partial(const float* st, float* part)
 {
     const int tid = threadIdx.x;
@@ -50,6 +88,54 @@ __device__ __forceinline__ void write_partial(const float* st, float* part)
     }
 }
 
+// Whole block: out = sum_s acc_s 2^(m_s - M) / sum_s l_s 2^(m_s - M) over `used` partials, to bf16.
+// lds: at least 2 * kMaxSplits + 8 floats.  Every thread of the block must call it.
+__device__ __forceinline__ void merge_partials_block(const float* __restrict__ p, int used,
+                                                     uint16_t* __restrict__ out, float* lds)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    float* w = lds;                       // [kMaxSplits] weights 2^(m_s - M)
+    float* red = lds + kMaxSplits;        // [8]
+    float* half = lds + kMaxSplits + 8;   // [128]
+    float my_m = kNegInf, my_l = 0.f;
+    if (tid < used) {
+        my_m = p[tid * kPartStride + kHeadDim];
+        my_l = p[tid * kPartStride + kHeadDim + 1];
+    }
+    float M = my_m;
+    for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o, kWave));
+    if (lane == 0) red[wave] = M;
+    __syncthreads();
+    M = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const float my_w = (tid < used && M != kNegInf) ? exp2f(my_m - M) : 0.f;
+    if (tid < kMaxSplits) w[tid] = my_w;
+    float den = my_l * my_w;
+    for (int o = 32; o > 0; o >>= 1) den += __shfl_xor(den, o, kWave);
+    if (lane == 0) red[4 + wave] = den;
+    __syncthreads();
+    den = (red[4] + red[5]) + (red[6] + red[7]);
+
+    const int ch = tid & (kHeadDim - 1), h = tid >> 7;       // two thread halves take alternate partials
+    float num = 0.f;
+    int s = h;
+#pragma unroll 1
+    for (; s + 14 < used; s += 16) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = p[(s + 2 * u) * kPartStride + ch];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) num = fmaf(v[u], w[s + 2 * u], num);
+    }
+    for (; s < used; s += 2) num = fmaf(p[s * kPartStride + ch], w[s], num);
+    if (h == 1) half[ch] = num;
+    __syncthreads();
+    if (h == 0) {
+        num += half[ch];
+        const float o = den > 0.f ? num / den : 0.f;
+        out[ch] = (uint16_t)f32_to_bf16(o);
+    }
+}
+
 template <bool PAGED>
 __global__ __launch_bounds__(256) void gather_attend_kernel(KvView c, const uint16_t* __restrict__ q,
                                                             const int32_t* __restrict__ idx,
@@ -63,14 +149,21 @@ __global__ __launch_bounds__(256) void gather_attend_kernel(KvView c, const uint
     const int slot = tid >> 4;                       // 0..15
     const int split = blockIdx.x, hq = blockIdx.y, b = blockIdx.z, kvh = hq / group;
     const int64_t bh = (int64_t)b * n_q_heads + hq;
-    const int cnt = min(count[bh], k_max);
+    const int32_t* my_idx = idx + bh * k_max;
     const int begin = split * chunk;
+
+    // the first index loads do not wait for the count: slots past it are valid memory, their
+    // contents are only used once known to be below the count
+    int tok[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) tok[i] = my_idx[min(begin + i * kSlots + slot, k_max - 1)];
+    const int cnt = min(count[bh], k_max);
+    const uint4 qraw = *reinterpret_cast<const uint4*>(q + bh * kHeadDim + sub * 8);
     if (begin >= cnt) return;                        // the merge kernel skips unused splits
     const int end = min(begin + chunk, cnt);
-    const int32_t* my_idx = idx + bh * k_max;
 
     float qf[8];
-    unpack8(*reinterpret_cast<const uint4*>(q + bh * kHeadDim + sub * 8), qf);
+    unpack8(qraw, qf);
 #pragma unroll
     for (int i = 0; i < 8; ++i) qf[i] *= scale_log2e;
 
@@ -78,46 +171,46 @@ __global__ __launch_bounds__(256) void gather_attend_kernel(KvView c, const uint
 #pragma unroll
     for (int i = 0; i < 8; ++i) acc[i] = 0.f;
 
-    for (int base = begin; base < end; base += kRowsPerIter) {
-        uint4 kr[4], vr[4];
-        bool ok[4];
+    const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
+    uint4 kr[4], vr[4];
+    bool ok[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int r = base + i * kSlots + slot;
-            ok[i] = r < end;
-            const int tok = my_idx[ok[i] ? r : end - 1];
-            const int64_t row = row_of<PAGED>(c, b, kvh, tok);
+    for (int i = 0; i < 4; ++i) {
+        ok[i] = begin + i * kSlots + slot < end;
+        kr[i] = zero4;
+        vr[i] = zero4;
+        if (ok[i]) {
+            const int64_t row = row_of<PAGED>(c, b, kvh, tok[i]);
             kr[i] = load_row16(c.k, row, sub);
             vr[i] = load_row16(c.v, row, sub);
+        }
+    }
+    for (int base = begin; base < end; base += kRowsPerIter) {
+        // issue the next 64 rows before consuming the current ones
+        const int nbase = base + kRowsPerIter;
+        uint4 kn[4], vn[4];
+        bool okn[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int r = nbase + i * kSlots + slot;
+            okn[i] = r < end;
+            kn[i] = zero4;
+            vn[i] = zero4;
+            if (okn[i]) {
+                const int64_t row = row_of<PAGED>(c, b, kvh, my_idx[r]);
+                kn[i] = load_row16(c.k, row, sub);
+                vn[i] = load_row16(c.v, row, sub);
+            }
         }
         float x[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            float kf[8];
-            unpack8(kr[i], kf);
-            float d = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) d = fmaf(qf[e], kf[e], d);
-            d = row16_sum(d);
+            const float d = dot8_row16(qf, kr[i]);
             x[i] = ok[i] ? d : kNegInf;
         }
-        const float m_new = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), m);
-        const float ref = (m_new == kNegInf) ? 0.f : m_new;      // a group may have seen no valid row yet
-        const float alpha = exp2f(m - ref);
-        float p[4];
+        absorb4(x, vr, m, l, acc);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) p[i] = exp2f(x[i] - ref);
-        l = l * alpha + (p[0] + p[1]) + (p[2] + p[3]);
-#pragma unroll
-        for (int e = 0; e < 8; ++e) acc[e] *= alpha;
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            float vf[8];
-            unpack8(vr[i], vf);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[e] = fmaf(p[i], vf[e], acc[e]);
-        }
-        m = m_new;
+        for (int i = 0; i < 4; ++i) { kr[i] = kn[i]; vr[i] = vn[i]; ok[i] = okn[i]; }
     }
 
     // a group that saw no valid row keeps m = -inf, l = 0 (possible when end - begin < 16)
@@ -142,60 +235,63 @@ __global__ __launch_bounds__(256) void dense_attend_kernel(KvView c, const uint1
     const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int n = min(c.seq_lens[b], n_cap);
     const int begin = split * chunk;
+    const int64_t bh0 = (int64_t)b * n_q_heads + kvh * G;
     if (begin >= n) return;
     const int end = min(begin + chunk, n);
 
     float qf[G][8], acc[G][8], m[G], l[G];
 #pragma unroll
     for (int j = 0; j < G; ++j) {
-        const int64_t bh = (int64_t)b * n_q_heads + kvh * G + j;
-        unpack8(*reinterpret_cast<const uint4*>(q + bh * kHeadDim + sub * 8), qf[j]);
+        unpack8(*reinterpret_cast<const uint4*>(q + (bh0 + j) * kHeadDim + sub * 8), qf[j]);
         m[j] = kNegInf;
         l[j] = 0.f;
 #pragma unroll
         for (int e = 0; e < 8; ++e) { qf[j][e] *= scale_log2e; acc[j][e] = 0.f; }
     }
 
-    for (int base = begin; base < end; base += kRowsPerIter) {
-        uint4 kr[4], vr[4];
-        bool ok[4];
+    const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
+    uint4 kr[4], vr[4];
+    bool ok[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int t = base + i * kSlots + slot;
-            ok[i] = t < end;
-            const int64_t row = row_of<PAGED>(c, b, kvh, ok[i] ? t : end - 1);
+    for (int i = 0; i < 4; ++i) {
+        const int t = begin + i * kSlots + slot;
+        ok[i] = t < end;
+        kr[i] = zero4;
+        vr[i] = zero4;
+        if (ok[i]) {
+            const int64_t row = row_of<PAGED>(c, b, kvh, t);
             kr[i] = load_row16(c.k, row, sub);
             vr[i] = load_row16(c.v, row, sub);
         }
-        float kf[4][8], vf[4][8];
+    }
+    for (int base = begin; base < end; base += kRowsPerIter) {
+        const int nbase = base + kRowsPerIter;
+        uint4 kn[4], vn[4];
+        bool okn[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { unpack8(kr[i], kf[i]); unpack8(vr[i], vf[i]); }
+        for (int i = 0; i < 4; ++i) {
+            const int t = nbase + i * kSlots + slot;
+            okn[i] = t < end;
+            kn[i] = zero4;
+            vn[i] = zero4;
+            if (okn[i]) {
+                const int64_t row = row_of<PAGED>(c, b, kvh, t);
+                kn[i] = load_row16(c.k, row, sub);
+                vn[i] = load_row16(c.v, row, sub);
+            }
+        }
 #pragma unroll
         for (int j = 0; j < G; ++j) {
             float x[4];
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
-                float d = 0.f;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) d = fmaf(qf[j][e], kf[i][e], d);
-                d = row16_sum(d);
+                const float d = dot8_row16(qf[j], kr[i]);
                 x[i] = ok[i] ? d : kNegInf;
             }
-            const float m_new = fmaxf(fmaxf(fmaxf(x[0], x[1]), fmaxf(x[2], x[3])), m[j]);
-            const float ref = (m_new == kNegInf) ? 0.f : m_new;
-            const float alpha = exp2f(m[j] - ref);
-            float p[4];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) p[i] = exp2f(x[i] - ref);
-            l[j] = l[j] * alpha + (p[0] + p[1]) + (p[2] + p[3]);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[j][e] *= alpha;
-#pragma unroll
-            for (int i = 0; i < 4; ++i)
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[j][e] = fmaf(p[i], vf[i][e], acc[j][e]);
-            m[j] = m_new;
+            absorb4(x, vr, m[j], l[j], acc[j]);
         }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { kr[i] = kn[i]; vr[i] = vn[i]; ok[i] = okn[i]; }
     }
 
     float* mine = st + slot * kPartStride;
@@ -206,34 +302,24 @@ __global__ __launch_bounds__(256) void dense_attend_kernel(KvView c, const uint1
         for (int e = 0; e < 8; ++e) mine[sub * 8 + e] = acc[j][e];
         if (sub == 0) { mine[kHeadDim] = m[j]; mine[kHeadDim + 1] = l[j]; }
         __syncthreads();
-        const int64_t bh = (int64_t)b * n_q_heads + kvh * G + j;
-        write_partial(st, part + (bh * n_splits + split) * kPartStride);
+        write_partial(st, part + ((bh0 + j) * n_splits + split) * kPartStride);
     }
 }
 
-// Merge split partials of one (sequence, query head): out = sum_s acc_s 2^(m_s - M) / sum_s l_s 2^(m_s - M).
-// lens: per head (count, PER_HEAD) or per sequence (seq_lens); splits beyond ceil(len / chunk) were not written.
+// Merge the split partials of one (sequence, query head).  lens: per head (count, PER_HEAD) or per
+// sequence (seq_lens); splits beyond ceil(len / chunk) were not written.  len = 0 gives a zero row.
 template <bool PER_HEAD>
-__global__ __launch_bounds__(128) void merge_partials_kernel(const float* __restrict__ part,
+__global__ __launch_bounds__(256) void merge_partials_kernel(const float* __restrict__ part,
                                                              const int32_t* __restrict__ lens, int len_cap,
                                                              int n_q_heads, int chunk, int n_splits,
                                                              uint16_t* __restrict__ out)
 {
-    const int hq = blockIdx.x, b = blockIdx.y, ch = threadIdx.x;
+    __shared__ float lds[2 * kMaxSplits + 8];
+    const int hq = blockIdx.x, b = blockIdx.y;
     const int64_t bh = (int64_t)b * n_q_heads + hq;
     const int len = min(PER_HEAD ? lens[bh] : lens[b], len_cap);
     const int used = min(n_splits, (len + chunk - 1) / chunk);
-    const float* p = part + bh * n_splits * kPartStride;
-    float M = kNegInf;
-    for (int s = 0; s < used; ++s) M = fmaxf(M, p[s * kPartStride + kHeadDim]);
-    float num = 0.f, den = 0.f;
-    for (int s = 0; s < used; ++s) {
-        const float w = exp2f(p[s * kPartStride + kHeadDim] - M);
-        num = fmaf(p[s * kPartStride + ch], w, num);
-        den = fmaf(p[s * kPartStride + kHeadDim + 1], w, den);
-    }
-    const float o = (used > 0 && den > 0.f) ? num / den : 0.f;
-    out[bh * kHeadDim + ch] = (uint16_t)f32_to_bf16(o);
+    merge_partials_block(part + bh * n_splits * kPartStride, used, out + bh * kHeadDim, lds);
 }
 
 constexpr float kLog2e = 1.4426950408889634f;
@@ -247,13 +333,13 @@ hipError_t launch_gather_attend(const KvView& kv, bool paged, int group, const u
 {
     const dim3 grid(n_splits, n_q_heads, batch), block(256);
     if (paged)
-        gather_attend_kernel<true><<<grid, block, 0, stream>>>(kv, q, idx, count, n_q_heads, group, k_max,
-                                                               chunk, n_splits, scale * kLog2e, part);
+        gather_attend_kernel<true><<<grid, block, 0, stream>>>(kv, q, idx, count, n_q_heads, group, k_max, chunk,
+                                                               n_splits, scale * kLog2e, part);
     else
-        gather_attend_kernel<false><<<grid, block, 0, stream>>>(kv, q, idx, count, n_q_heads, group, k_max,
-                                                                chunk, n_splits, scale * kLog2e, part);
-    merge_partials_kernel<true><<<dim3(n_q_heads, batch), 128, 0, stream>>>(part, count, k_max, n_q_heads,
-                                                                            chunk, n_splits, out);
+        gather_attend_kernel<false><<<grid, block, 0, stream>>>(kv, q, idx, count, n_q_heads, group, k_max, chunk,
+                                                                n_splits, scale * kLog2e, part);
+    merge_partials_kernel<true><<<dim3(n_q_heads, batch), block, 0, stream>>>(part, count, k_max, n_q_heads, chunk,
+                                                                              n_splits, out);
     return hipGetLastError();
 }
 
@@ -264,11 +350,11 @@ static void launch_dense_g(const KvView& kv, bool paged, const uint16_t* q, int 
 {
     const dim3 grid(n_splits, kv.n_kv_heads, batch), block(256);
     if (paged)
-        dense_attend_kernel<G, true><<<grid, block, 0, stream>>>(kv, q, n_q_heads, max_seq_len, chunk,
-                                                                 n_splits, scale * kLog2e, part);
+        dense_attend_kernel<G, true><<<grid, block, 0, stream>>>(kv, q, n_q_heads, max_seq_len, chunk, n_splits,
+                                                                 scale * kLog2e, part);
     else
-        dense_attend_kernel<G, false><<<grid, block, 0, stream>>>(kv, q, n_q_heads, max_seq_len, chunk,
-                                                                  n_splits, scale * kLog2e, part);
+        dense_attend_kernel<G, false><<<grid, block, 0, stream>>>(kv, q, n_q_heads, max_seq_len, chunk, n_splits,
+                                                                  scale * kLog2e, part);
 }
 
 hipError_t launch_dense_attend(const KvView& kv, bool paged, int group, const uint16_t* q,
@@ -282,8 +368,8 @@ hipError_t launch_dense_attend(const KvView& kv, bool paged, int group, const ui
     case 8: launch_dense_g<8>(kv, paged, q, batch, n_q_heads, max_seq_len, chunk, n_splits, scale, part, stream); break;
     default: return hipErrorInvalidValue;
     }
-    merge_partials_kernel<false><<<dim3(n_q_heads, batch), 128, 0, stream>>>(part, kv.seq_lens, max_seq_len,
-                                                                             n_q_heads, chunk, n_splits, out);
+    merge_partials_kernel<false><<<dim3(n_q_heads, batch), 256, 0, stream>>>(part, kv.seq_lens, max_seq_len, n_q_heads,
+                                                                             chunk, n_splits, out);
     return hipGetLastError();
 }
 

@@ -10,6 +10,7 @@ constexpr int kBits = 32;         // signature width
 constexpr int kBins = 33;         // Hamming similarity takes values 0..32
 constexpr int kPage = 16;         // tokens per page in the paged layout
 constexpr int kWave = 64;
+constexpr int kMaxScanUnits = 960;  // units per sequence the scan kernel can stage in 64 KiB of LDS
 constexpr int kPartStride = 132;  // floats per split partial: acc[128], m, l, pad
 
 // Plain view of the caller's KV cache, passed to kernels by value.

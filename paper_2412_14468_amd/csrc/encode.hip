@@ -66,34 +66,35 @@ __device__ int mlp_gemv(const MlpView& phi, int head, float (*act)[kVecPerBlock]
 // MODE 0: queries.  x = q [B][H][128]; codes -> q_codes [B][H]; vector index = b.
 // MODE 1: appended keys.  x = k_new [B][H][n_new][128]; vector index = b * n_new + j; the K and V rows
 //         are copied to cache position seq_lens[b] + j and the code stored there.
-template <int MODE, bool PAGED>
-__global__ __launch_bounds__(256) void encode_vec_kernel(MlpView phi, int n_heads, const uint16_t* __restrict__ x,
-                                                         const uint16_t* __restrict__ v_new, int n_vec, int n_new,
-                                                         uint32_t* __restrict__ q_codes, KvView c, int n_cap)
+template <int MODE>
+__device__ __forceinline__ void load_vectors(float (*act0)[kMaxWidth], int n_heads, int head, int v0,
+                                             const uint16_t* __restrict__ x, int n_vec, int n_new)
 {
-    __shared__ float act[2][kVecPerBlock][kMaxWidth];
-    __shared__ float red[kVecPerBlock * 256];
     const int tid = threadIdx.x;
-    const int head = blockIdx.x, v0 = blockIdx.y * kVecPerBlock;
-    const int d = phi.dims[0];                                     // 128
-
-    for (int o = tid; o < kVecPerBlock * d; o += 256) {
-        const int v = o / d, i = o - v * d, vec = v0 + v;
+    for (int o = tid; o < kVecPerBlock * kHeadDim; o += 256) {
+        const int v = o / kHeadDim, i = o - v * kHeadDim, vec = v0 + v;
         float val = 0.f;
         if (vec < n_vec) {
             const int b = MODE == 0 ? vec : vec / n_new, jn = MODE == 0 ? 0 : vec - b * n_new;
             const int64_t src = MODE == 0 ? ((int64_t)b * n_heads + head)
                                           : (((int64_t)b * n_heads + head) * n_new + jn);
-            val = __uint_as_float((uint32_t)x[src * d + i] << 16);
+            val = __uint_as_float((uint32_t)x[src * kHeadDim + i] << 16);
         }
-        act[0][v][i] = val;
+        act0[v][i] = val;
     }
-    __syncthreads();
-    const int cur = mlp_gemv(phi, head, act, red);
+}
 
+// a: [kVecPerBlock][kMaxWidth] pre-sign activations of the last layer
+template <int MODE, bool PAGED>
+__device__ __forceinline__ void store_codes(const float (*a)[kMaxWidth], int n_heads, int head, int v0,
+                                            const uint16_t* __restrict__ x, const uint16_t* __restrict__ v_new,
+                                            int n_vec, int n_new, uint32_t* __restrict__ q_codes,
+                                            const KvView& c, int n_cap)
+{
     // thread (v = tid / 32, j = tid % 32) owns bit j of vector v; a wave ballot packs two vectors
+    const int tid = threadIdx.x;
     const int v = tid >> 5, j = tid & 31, vec = v0 + v;
-    const uint64_t mask = __ballot(act[cur][v][j] > 0.f);
+    const uint64_t mask = __ballot(a[v][j] > 0.f);
     const uint32_t code = (uint32_t)((tid & 32) ? (mask >> 32) : mask);
     if (vec < n_vec) {
         const int b = MODE == 0 ? vec : vec / n_new, jn = MODE == 0 ? 0 : vec - b * n_new;
@@ -109,6 +110,106 @@ __global__ __launch_bounds__(256) void encode_vec_kernel(MlpView phi, int n_head
             *to = *from;
         }
     }
+}
+
+// Any supported network shape; weights are fetched inside the layer loops.
+template <int MODE, bool PAGED>
+__global__ __launch_bounds__(256) void encode_vec_kernel(MlpView phi, int n_heads, const uint16_t* __restrict__ x,
+                                                         const uint16_t* __restrict__ v_new, int n_vec, int n_new,
+                                                         uint32_t* __restrict__ q_codes, KvView c, int n_cap)
+{
+    __shared__ float act[2][kVecPerBlock][kMaxWidth];
+    __shared__ float red[kVecPerBlock * 256];
+    const int head = blockIdx.x, v0 = blockIdx.y * kVecPerBlock;
+    load_vectors<MODE>(act[0], n_heads, head, v0, x, n_vec, n_new);
+    __syncthreads();
+    const int cur = mlp_gemv(phi, head, act, red);
+    store_codes<MODE, PAGED>(act[cur], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+}
+
+// ---- shapes known at compile time: every thread fetches all its weights of all layers up front,
+// so the kernel costs about one trip to HBM instead of one per input row (the weights of a layer
+// are cold at every decode step: 80 KiB per head for 128-128-32).
+template <int DI, int DOUT>
+__device__ __forceinline__ void fetch_weights(const float* __restrict__ W, float (&w)[DI * DOUT / 256])
+{
+    constexpr int SPAN = DI * DOUT / 256;
+    const int j = threadIdx.x % DOUT, p = threadIdx.x / DOUT;
+#pragma unroll
+    for (int i = 0; i < SPAN; ++i) w[i] = W[(int64_t)(p * SPAN + i) * DOUT + j];
+}
+
+template <int DI, int DOUT>
+__device__ __forceinline__ void gemv_layer(const float (&w)[DI * DOUT / 256], const float* __restrict__ bias,
+                                           const float (*in)[kMaxWidth], float (*out)[kMaxWidth], float* red,
+                                           bool last)
+{
+    constexpr int SPAN = DI * DOUT / 256, PARTS = 256 / DOUT;
+    const int tid = threadIdx.x, j = tid % DOUT, p = tid / DOUT;
+    float acc[kVecPerBlock];
+#pragma unroll
+    for (int v = 0; v < kVecPerBlock; ++v) acc[v] = 0.f;
+#pragma unroll
+    for (int i = 0; i < SPAN; ++i)
+#pragma unroll
+        for (int v = 0; v < kVecPerBlock; ++v) acc[v] = fmaf(in[v][p * SPAN + i], w[i], acc[v]);
+#pragma unroll
+    for (int v = 0; v < kVecPerBlock; ++v) red[(p * kVecPerBlock + v) * DOUT + j] = acc[v];
+    __syncthreads();
+    for (int o = tid; o < kVecPerBlock * DOUT; o += 256) {
+        const int v = o / DOUT, jj = o - v * DOUT;
+        float z = 0.f;
+#pragma unroll
+        for (int pp = 0; pp < PARTS; ++pp) z += red[(pp * kVecPerBlock + v) * DOUT + jj];
+        if (bias) z += bias[jj];
+        out[v][jj] = last ? z : silu(z);
+    }
+    __syncthreads();
+}
+
+// NL layers: 128 -> D1 -> D2 -> 32 (NL = 3), 128 -> D1 -> 32 (NL = 2), 128 -> 32 (NL = 1).
+template <int MODE, bool PAGED, int NL, int D1, int D2>
+__global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int n_heads,
+                                                               const uint16_t* __restrict__ x,
+                                                               const uint16_t* __restrict__ v_new, int n_vec,
+                                                               int n_new, uint32_t* __restrict__ q_codes,
+                                                               KvView c, int n_cap)
+{
+    __shared__ float act[2][kVecPerBlock][kMaxWidth];
+    __shared__ float red[kVecPerBlock * 256];
+    const int head = blockIdx.x, v0 = blockIdx.y * kVecPerBlock;
+    constexpr int O0 = NL == 1 ? kBits : D1;            // outputs of layer 0
+    constexpr int I1 = D1, O1 = NL == 2 ? kBits : D2;   // layer 1 (NL >= 2)
+    constexpr int I2 = D2;                              // layer 2 (NL == 3), 32 outputs
+    float w0[kHeadDim * O0 / 256];
+    float w1[NL >= 2 ? I1 * O1 / 256 : 1];
+    float w2[NL == 3 ? I2 * kBits / 256 : 1];
+    fetch_weights<kHeadDim, O0>(phi.W[0] + (int64_t)head * kHeadDim * O0, w0);
+    if constexpr (NL >= 2) fetch_weights<I1, O1>(phi.W[1] + (int64_t)head * I1 * O1, w1);
+    if constexpr (NL == 3) fetch_weights<I2, kBits>(phi.W[2] + (int64_t)head * I2 * kBits, w2);
+    load_vectors<MODE>(act[0], n_heads, head, v0, x, n_vec, n_new);
+    __syncthreads();
+    gemv_layer<kHeadDim, O0>(w0, phi.bias[0] ? phi.bias[0] + (int64_t)head * O0 : nullptr, act[0], act[1], red, NL == 1);
+    if constexpr (NL >= 2)
+        gemv_layer<I1, O1>(w1, phi.bias[1] ? phi.bias[1] + (int64_t)head * O1 : nullptr, act[1], act[0], red, NL == 2);
+    if constexpr (NL == 3)
+        gemv_layer<I2, kBits>(w2, phi.bias[2] ? phi.bias[2] + (int64_t)head * kBits : nullptr, act[0], act[1], red, true);
+    store_codes<MODE, PAGED>(act[NL & 1], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+}
+
+template <int MODE, bool PAGED>
+void launch_encode_vec(const MlpView& phi, dim3 grid, int n_heads, const uint16_t* x, const uint16_t* v_new,
+                       int n_vec, int n_new, uint32_t* q_codes, const KvView& c, int n_cap, hipStream_t stream)
+{
+    const int nl = phi.n_layers, d1 = phi.dims[1], d2 = phi.dims[2];
+    if (nl == 1)
+        encode_vec_fixed_kernel<MODE, PAGED, 1, 32, 32><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+    else if (nl == 2 && d1 == 128)
+        encode_vec_fixed_kernel<MODE, PAGED, 2, 128, 32><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+    else if (nl == 3 && d1 == 128 && d2 == 128)
+        encode_vec_fixed_kernel<MODE, PAGED, 3, 128, 128><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+    else
+        encode_vec_kernel<MODE, PAGED><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
 }
 
 __global__ void bump_seq_lens_kernel(int32_t* seq_lens, int batch, int n_new)
@@ -254,7 +355,7 @@ hipError_t launch_encode_query(const MlpView& phi, const uint16_t* q, int batch,
 {
     const dim3 grid(n_heads, (batch + kVecPerBlock - 1) / kVecPerBlock);
     KvView none{};
-    encode_vec_kernel<0, false><<<grid, 256, 0, stream>>>(phi, n_heads, q, nullptr, batch, 1, q_codes, none, 0);
+    launch_encode_vec<0, false>(phi, grid, n_heads, q, nullptr, batch, 1, q_codes, none, 0, stream);
     return hipGetLastError();
 }
 
@@ -270,9 +371,9 @@ hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
             const int n_vec = (int)(batch * n_new);
             const dim3 grid(H, (n_vec + kVecPerBlock - 1) / kVecPerBlock);
             if (paged)
-                encode_vec_kernel<1, true><<<grid, 256, 0, stream>>>(phi, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len);
+                launch_encode_vec<1, true>(phi, grid, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len, stream);
             else
-                encode_vec_kernel<1, false><<<grid, 256, 0, stream>>>(phi, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len);
+                launch_encode_vec<1, false>(phi, grid, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len, stream);
         } else {
             const dim3 cgrid((unsigned)((n_new * 16 + 255) / 256), H, batch);
             const dim3 egrid((unsigned)((n_new + kTile - 1) / kTile), H, batch);

@@ -68,13 +68,17 @@ __global__ __launch_bounds__(256) void score_hist_kernel(KvView c, const uint32_
     }
 }
 
+// One block per (sequence, query head).  The head's [33][n_units] histogram tile is staged in LDS
+// with one round of 16-byte loads; everything after that reads LDS only.
+// lds_pitch: row pitch of the tile in uint16, a multiple of 8 and >= the number of units in use.
 __global__ __launch_bounds__(256) void topk_scan_kernel(const int32_t* __restrict__ seq_lens,
                                                         const int32_t* __restrict__ k_per_seq, int k_max,
                                                         int n_q_heads, int n_cap, int unit_tokens, int units_pitch,
-                                                        const uint16_t* __restrict__ unit_hist,
+                                                        int lds_pitch, const uint16_t* __restrict__ unit_hist,
                                                         int2* __restrict__ unit_off, int2* __restrict__ sel,
                                                         int32_t* __restrict__ count, uint8_t* __restrict__ threshold)
 {
+    extern __shared__ uint16_t tile[];          // [kBins][lds_pitch]
     __shared__ int total[kBins];
     __shared__ int s_T, s_r;
     __shared__ int wave_gt[4], wave_eq[4];
@@ -94,10 +98,19 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(const int32_t* __restric
     }
     const int n_units = (n + unit_tokens - 1) / unit_tokens;
     const uint16_t* h = unit_hist + bh * kBins * units_pitch;
+    {
+        const int vec_per_row = (n_units + 7) >> 3;            // 8 counts per 16-byte load
+        for (int v = tid; v < kBins * vec_per_row; v += 256) {
+            const int s = v / vec_per_row, cvec = v - s * vec_per_row;
+            *reinterpret_cast<uint4*>(tile + s * lds_pitch + cvec * 8) =
+                *reinterpret_cast<const uint4*>(h + (int64_t)s * units_pitch + cvec * 8);
+        }
+    }
+    __syncthreads();
 
     for (int s = wave; s < kBins; s += 4) {
         int acc = 0;
-        for (int u = lane; u < n_units; u += kWave) acc += h[(int64_t)s * units_pitch + u];
+        for (int u = lane; u < n_units; u += kWave) acc += tile[s * lds_pitch + u];
         acc = wave_sum_i32(acc);
         if (lane == 0) total[s] = acc;
     }
@@ -119,8 +132,8 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(const int32_t* __restric
     const int u0 = tid * per, u1 = min(n_units, u0 + per);
     int my_gt = 0, my_eq = 0;
     for (int u = u0; u < u1; ++u) {
-        for (int s = T + 1; s < kBins; ++s) my_gt += h[(int64_t)s * units_pitch + u];
-        my_eq += h[(int64_t)T * units_pitch + u];
+        for (int s = T + 1; s < kBins; ++s) my_gt += tile[s * lds_pitch + u];
+        my_eq += tile[T * lds_pitch + u];
     }
     int inc_gt = my_gt, inc_eq = my_eq;         // inclusive scan inside the wave
     for (int o = 1; o < kWave; o <<= 1) {
@@ -135,8 +148,8 @@ __global__ __launch_bounds__(256) void topk_scan_kernel(const int32_t* __restric
     int2* off = unit_off + bh * units_pitch;
     for (int u = u0; u < u1; ++u) {
         int gt = 0;
-        for (int s = T + 1; s < kBins; ++s) gt += h[(int64_t)s * units_pitch + u];
-        const int eq = h[(int64_t)T * units_pitch + u];
+        for (int s = T + 1; s < kBins; ++s) gt += tile[s * lds_pitch + u];
+        const int eq = tile[T * lds_pitch + u];
         const int left = r - run_eq;            // quota still open when this unit starts
         const int quota = left >= eq ? kAllTies : max(left, 0);
         off[u] = make_int2(run_gt + min(run_eq, r), quota);
@@ -243,9 +256,12 @@ hipError_t launch_g(const KvView& kv, bool paged, const uint32_t* q_codes, int b
             score_hist_kernel<G, false><<<grid, block, 0, stream>>>(kv, q_codes, n_q_heads, max_seq_len, unit_tokens,
                                                                      sc.units_pitch, sc.unit_hist);
     }
-    topk_scan_kernel<<<dim3(n_q_heads, batch), block, 0, stream>>>(kv.seq_lens, k_per_seq, k_max, n_q_heads,
-                                                                    max_seq_len, unit_tokens, sc.units_pitch, sc.unit_hist,
-                                                                    sc.unit_off, sc.sel, count, threshold);
+    const int lds_pitch = ((n_units > 0 ? n_units : 1) + 7) / 8 * 8;
+    const size_t lds_bytes = sizeof(uint16_t) * kBins * (size_t)lds_pitch;      // <= 64 KiB: n_units <= kMaxScanUnits
+    topk_scan_kernel<<<dim3(n_q_heads, batch), block, lds_bytes, stream>>>(kv.seq_lens, k_per_seq, k_max, n_q_heads,
+                                                                            max_seq_len, unit_tokens, sc.units_pitch,
+                                                                            lds_pitch, sc.unit_hist, sc.unit_off, sc.sel,
+                                                                            count, threshold);
     if (n_units > 0) {
         if (paged)
             topk_compact_kernel<G, true><<<grid, block, 0, stream>>>(kv, q_codes, n_q_heads, max_seq_len, unit_tokens,
