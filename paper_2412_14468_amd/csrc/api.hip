@@ -13,9 +13,9 @@ struct hashattn_ctx {
     int device;
     int group;
     // TOPK scratch
-    uint16_t* unit_hist;
-    int2* unit_off;
-    int2* sel;
+    uint16_t* unit_cum;
+    int32_t* ghist;
+    int32_t* tickets;
     int32_t units_pitch;
     // split partials shared by GATHER-ATT and the dense kernel
     float* part;
@@ -204,20 +204,24 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
     pitch = (pitch + 7) / 8 * 8;
     ctx->units_pitch = (int32_t)pitch;
     const int64_t hist_bytes = bh * ha::kBins * pitch * (int64_t)sizeof(uint16_t);
-    const int64_t off_bytes = bh * pitch * (int64_t)sizeof(int2);
-    const int64_t sel_bytes = bh * (int64_t)sizeof(int2);
+    const int64_t ghist_bytes = bh * ha::kBins * (int64_t)sizeof(int32_t);
+    const int64_t ticket_bytes = (int64_t)cfg->max_batch * cfg->n_kv_heads * (int64_t)sizeof(int32_t);
     int64_t splits = (cfg->max_context + 63) / 64;               // dense needs more splits than gather
     int64_t want = 4096 / bh; if (want < 8) want = 8;
     if (splits > want) splits = want;
     if (splits > kMaxSplits) splits = kMaxSplits;
     ctx->part_floats = bh * splits * ha::kPartStride;
     const int64_t part_bytes = ctx->part_floats * (int64_t)sizeof(float);
-    ctx->scratch_bytes = hist_bytes + off_bytes + sel_bytes + part_bytes;
+    ctx->scratch_bytes = hist_bytes + ghist_bytes + ticket_bytes + part_bytes;
 
-    if ((e = hipMalloc(reinterpret_cast<void**>(&ctx->unit_hist), hist_bytes)) != hipSuccess ||
-        (e = hipMalloc(reinterpret_cast<void**>(&ctx->unit_off), off_bytes)) != hipSuccess ||
-        (e = hipMalloc(reinterpret_cast<void**>(&ctx->sel), sel_bytes)) != hipSuccess ||
-        (e = hipMalloc(reinterpret_cast<void**>(&ctx->part), part_bytes)) != hipSuccess) {
+    // the score histograms and tickets must read zero when the first call starts; later calls leave them so
+    if ((e = hipMalloc(reinterpret_cast<void**>(&ctx->unit_cum), hist_bytes)) != hipSuccess ||
+        (e = hipMalloc(reinterpret_cast<void**>(&ctx->ghist), ghist_bytes)) != hipSuccess ||
+        (e = hipMalloc(reinterpret_cast<void**>(&ctx->tickets), ticket_bytes)) != hipSuccess ||
+        (e = hipMalloc(reinterpret_cast<void**>(&ctx->part), part_bytes)) != hipSuccess ||
+        (e = hipMemset(ctx->ghist, 0, ghist_bytes)) != hipSuccess ||
+        (e = hipMemset(ctx->tickets, 0, ticket_bytes)) != hipSuccess ||
+        (e = hipDeviceSynchronize()) != hipSuccess) {
         hashattn_destroy(ctx);
         return fail(nullptr, HASHATTN_HIP_ERROR, "create: allocating %lld scratch bytes: %s",
                     (long long)ctx->scratch_bytes, hipGetErrorString(e));
@@ -229,9 +233,9 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
 hashattn_status hashattn_destroy(hashattn_ctx* ctx)
 {
     if (!ctx) return HASHATTN_OK;
-    if (ctx->unit_hist) (void)hipFree(ctx->unit_hist);
-    if (ctx->unit_off) (void)hipFree(ctx->unit_off);
-    if (ctx->sel) (void)hipFree(ctx->sel);
+    if (ctx->unit_cum) (void)hipFree(ctx->unit_cum);
+    if (ctx->ghist) (void)hipFree(ctx->ghist);
+    if (ctx->tickets) (void)hipFree(ctx->tickets);
     if (ctx->part) (void)hipFree(ctx->part);
     delete ctx;
     return HASHATTN_OK;
@@ -294,7 +298,7 @@ hashattn_status hashattn_score_topk(hashattn_ctx* ctx, const uint32_t* q_codes, 
         return fail(ctx, HASHATTN_INVALID_ARG, "score_topk: 4-byte alignment required");
     if (k_max < 1) return fail(ctx, HASHATTN_INVALID_ARG, "score_topk: k_max %d < 1", k_max);
     if (k_max > ctx->cfg.max_k) return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "score_topk: k_max %d exceeds max_k %lld", k_max, (long long)ctx->cfg.max_k);
-    const ha::TopkScratch sc{ctx->unit_hist, ctx->unit_off, ctx->sel, ctx->units_pitch};
+    const ha::TopkScratch sc{ctx->unit_cum, ctx->ghist, ctx->tickets, ctx->units_pitch};
     const int unit = pick_unit_tokens(ctx, batch, cache->max_seq_len);
     const hipError_t e = ha::launch_score_topk(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group, q_codes, batch,
                                                ctx->cfg.n_q_heads, k_per_seq, k_max, cache->max_seq_len, unit, sc,

@@ -10,7 +10,7 @@ constexpr int kBits = 32;         // signature width
 constexpr int kBins = 33;         // Hamming similarity takes values 0..32
 constexpr int kPage = 16;         // tokens per page in the paged layout
 constexpr int kWave = 64;
-constexpr int kMaxScanUnits = 960;  // units per sequence the scan kernel can stage in 64 KiB of LDS
+constexpr int kMaxScanUnits = 960;  // most units per sequence: every block sums two table rows over the units before it
 constexpr int kPartStride = 132;  // floats per split partial: acc[128], m, l, pad
 
 // Plain view of the caller's KV cache, passed to kernels by value.
@@ -73,10 +73,34 @@ __device__ __forceinline__ float row16_sum(float x)
     return x;
 }
 
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int x)
+{
+    return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xf, 0xf, true);    // lanes shifted in from outside read 0
+}
+
+// Sum over the 64 lanes; every lane gets the total.  DPP inside 16-lane rows, readlane across rows.
 __device__ __forceinline__ int wave_sum_i32(int x)
 {
-    for (int o = 32; o > 0; o >>= 1) x += __shfl_xor(x, o, kWave);
-    return x;
+    x += dpp_i<0x128>(x);   // row_ror:8
+    x += dpp_i<0x124>(x);   // row_ror:4
+    x += dpp_i<0x122>(x);   // row_ror:2
+    x += dpp_i<0x121>(x);   // row_ror:1
+    return (__builtin_amdgcn_readlane(x, 0) + __builtin_amdgcn_readlane(x, 16)) +
+           (__builtin_amdgcn_readlane(x, 32) + __builtin_amdgcn_readlane(x, 48));
+}
+
+// Inclusive prefix sum over the 64 lanes (lane i gets x_0 + ... + x_i).
+__device__ __forceinline__ int wave_incl_scan_i32(int x)
+{
+    x += dpp_i<0x111>(x);   // row_shr:1
+    x += dpp_i<0x112>(x);   // row_shr:2
+    x += dpp_i<0x114>(x);   // row_shr:4
+    x += dpp_i<0x118>(x);   // row_shr:8
+    const int r0 = __builtin_amdgcn_readlane(x, 15), r1 = __builtin_amdgcn_readlane(x, 31),
+              r2 = __builtin_amdgcn_readlane(x, 47);
+    const int row = (int)(threadIdx.x & 63) >> 4;
+    return x + (row >= 1 ? r0 : 0) + (row >= 2 ? r1 : 0) + (row >= 3 ? r2 : 0);
 }
 
 // Number of set bits of a wave mask in lanes below the calling lane.

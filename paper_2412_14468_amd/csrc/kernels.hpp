@@ -14,9 +14,9 @@ struct MlpView {
 };
 
 struct TopkScratch {
-    uint16_t* unit_hist;   // [B][Hq][33][units_pitch]
-    int2* unit_off;        // [B][Hq][units_pitch]: {output offset, tie quota inside the unit}
-    int2* sel;             // [B][Hq]: {threshold T, unused}
+    uint16_t* unit_cum;    // [B][Hq][33][units_pitch]: per unit, #{score >= s}
+    int32_t* ghist;        // [B][Hq][33]: per head score counts; zero between calls
+    int32_t* tickets;      // [B][Hkv]: finished-block counters of topk_select; zero between calls
     int32_t units_pitch;
 };
 
