@@ -13,10 +13,9 @@ struct hashattn_ctx {
     int device;
     int group;
     // TOPK scratch
+    int32_t* blk_cum;
     uint16_t* unit_cum;
-    int32_t* ghist;
-    int32_t* tickets;
-    int32_t units_pitch;
+    int32_t blocks_pitch;
     // split partials shared by GATHER-ATT and the dense kernel
     float* part;
     int64_t part_floats;
@@ -27,7 +26,7 @@ struct hashattn_ctx {
 namespace {
 
 constexpr int kMinUnit = 256;          // tokens per wave unit: one 16-byte load per lane
-constexpr int kMaxUnit = 16384;        // keeps per-unit counts inside uint16
+constexpr int kMaxUnit = 2048;
 constexpr int kMaxSplits = 256;
 
 char g_create_err[256] = "";
@@ -120,16 +119,15 @@ ha::KvView view_of(const hashattn_ctx* ctx, const hashattn_kv* kv)
 }
 
 // Tokens per wave unit of SCORE/TOPK: small units fill the chip at short contexts, larger ones
-// keep the number of per-unit histograms down at long contexts.
+// keep the number of blocks (and of per-block tables every block has to sum) down at long contexts.
 int pick_unit_tokens(const hashattn_ctx* ctx, int batch, int max_seq_len)
 {
     const int64_t lanes = (int64_t)batch * ctx->cfg.n_kv_heads;
     int unit = kMinUnit;
-    // aim for about 8192 waves in flight over the whole grid, never more units than the scratch pitch
+    auto blocks = [&](int u) { return (max_seq_len + (int64_t)u * ha::kTopkWavesPerBlock - 1) / ((int64_t)u * ha::kTopkWavesPerBlock); };
+    // aim for at most about 8192 waves over the whole grid, never more blocks than the scratch pitch
     while (unit < kMaxUnit &&
-           (lanes * ((max_seq_len + unit - 1) / unit) > 8192 ||
-            (max_seq_len + unit - 1) / unit > ctx->units_pitch ||
-            (max_seq_len + unit - 1) / unit > ha::kMaxScanUnits))
+           (lanes * ((max_seq_len + unit - 1) / unit) > 8192 || blocks(unit) > ctx->blocks_pitch))
         unit *= 2;
     return unit;
 }
@@ -177,7 +175,7 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
     if (cfg->page_size != 0 && cfg->page_size != ha::kPage)
         return fail(nullptr, HASHATTN_UNSUPPORTED, "create: page_size %d, only 0 (contiguous) or 16", cfg->page_size);
     if (cfg->max_batch < 1 || cfg->max_batch > 65535) return fail(nullptr, HASHATTN_INVALID_ARG, "create: max_batch %d not in 1..65535", cfg->max_batch);
-    const int64_t context_limit = (int64_t)ha::kMaxScanUnits * kMaxUnit;       // 15.7 M tokens
+    const int64_t context_limit = (int64_t)ha::kMaxTopkBlocks * ha::kTopkWavesPerBlock * kMaxUnit;   // 4 Mi tokens
     if (cfg->max_context < 1 || cfg->max_context > context_limit)
         return fail(nullptr, HASHATTN_INVALID_ARG, "create: max_context %lld not in 1..%lld", (long long)cfg->max_context,
                     (long long)context_limit);
@@ -194,37 +192,26 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
     if (e != hipSuccess) { delete ctx; return fail(nullptr, HASHATTN_HIP_ERROR, "create: hipGetDevice: %s", hipGetErrorString(e)); }
 
     const int64_t bh = (int64_t)cfg->max_batch * cfg->n_q_heads;
-    // unit pitch: enough 256-token units for max_context, capped so that the per-unit histograms stay small
-    int64_t pitch = (cfg->max_context + kMinUnit - 1) / kMinUnit;
-    const int64_t min_pitch = (cfg->max_context + kMaxUnit - 1) / kMaxUnit;
-    const int64_t budget = (int64_t)(64 << 20) / (bh * ha::kBins * (int64_t)sizeof(uint16_t));   // 64 MiB of histograms
-    if (pitch > budget) pitch = budget;
-    if (pitch > ha::kMaxScanUnits) pitch = ha::kMaxScanUnits;
-    if (pitch < min_pitch) pitch = min_pitch;
-    pitch = (pitch + 7) / 8 * 8;
-    ctx->units_pitch = (int32_t)pitch;
-    const int64_t hist_bytes = bh * ha::kBins * pitch * (int64_t)sizeof(uint16_t);
-    const int64_t ghist_bytes = bh * ha::kBins * (int64_t)sizeof(int32_t);
-    const int64_t ticket_bytes = (int64_t)cfg->max_batch * cfg->n_kv_heads * (int64_t)sizeof(int32_t);
+    // per-block score tables: one block per 16 units of at least 256 tokens, at most kMaxTopkBlocks per sequence
+    int64_t pitch = (cfg->max_context + (int64_t)kMinUnit * ha::kTopkWavesPerBlock - 1) / ((int64_t)kMinUnit * ha::kTopkWavesPerBlock);
+    if (pitch > ha::kMaxTopkBlocks) pitch = ha::kMaxTopkBlocks;
+    ctx->blocks_pitch = (int32_t)pitch;
+    const int64_t hist_bytes = bh * pitch * ha::kCumRow * (int64_t)sizeof(int32_t);
+    const int64_t unit_bytes = bh * pitch * ha::kTopkWavesPerBlock * ha::kCumRow * (int64_t)sizeof(uint16_t);
     int64_t splits = (cfg->max_context + 63) / 64;               // dense needs more splits than gather
     int64_t want = 4096 / bh; if (want < 8) want = 8;
     if (splits > want) splits = want;
     if (splits > kMaxSplits) splits = kMaxSplits;
     ctx->part_floats = bh * splits * ha::kPartStride;
     const int64_t part_bytes = ctx->part_floats * (int64_t)sizeof(float);
-    ctx->scratch_bytes = hist_bytes + ghist_bytes + ticket_bytes + part_bytes;
+    ctx->scratch_bytes = hist_bytes + unit_bytes + part_bytes;
 
-    // the score histograms and tickets must read zero when the first call starts; later calls leave them so
-    if ((e = hipMalloc(reinterpret_cast<void**>(&ctx->unit_cum), hist_bytes)) != hipSuccess ||
-        (e = hipMalloc(reinterpret_cast<void**>(&ctx->ghist), ghist_bytes)) != hipSuccess ||
-        (e = hipMalloc(reinterpret_cast<void**>(&ctx->tickets), ticket_bytes)) != hipSuccess ||
-        (e = hipMalloc(reinterpret_cast<void**>(&ctx->part), part_bytes)) != hipSuccess ||
-        (e = hipMemset(ctx->ghist, 0, ghist_bytes)) != hipSuccess ||
-        (e = hipMemset(ctx->tickets, 0, ticket_bytes)) != hipSuccess ||
-        (e = hipDeviceSynchronize()) != hipSuccess) {
+    if ((e = hipMalloc(reinterpret_cast<void**>(&ctx->blk_cum), hist_bytes)) != hipSuccess ||
+        (e = hipMalloc(reinterpret_cast<void**>(&ctx->unit_cum), unit_bytes)) != hipSuccess ||
+        (e = hipMalloc(reinterpret_cast<void**>(&ctx->part), part_bytes)) != hipSuccess) {
+        const long long wanted = (long long)ctx->scratch_bytes;
         hashattn_destroy(ctx);
-        return fail(nullptr, HASHATTN_HIP_ERROR, "create: allocating %lld scratch bytes: %s",
-                    (long long)ctx->scratch_bytes, hipGetErrorString(e));
+        return fail(nullptr, HASHATTN_HIP_ERROR, "create: allocating %lld scratch bytes: %s", wanted, hipGetErrorString(e));
     }
     *out = ctx;
     return HASHATTN_OK;
@@ -233,9 +220,8 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
 hashattn_status hashattn_destroy(hashattn_ctx* ctx)
 {
     if (!ctx) return HASHATTN_OK;
+    if (ctx->blk_cum) (void)hipFree(ctx->blk_cum);
     if (ctx->unit_cum) (void)hipFree(ctx->unit_cum);
-    if (ctx->ghist) (void)hipFree(ctx->ghist);
-    if (ctx->tickets) (void)hipFree(ctx->tickets);
     if (ctx->part) (void)hipFree(ctx->part);
     delete ctx;
     return HASHATTN_OK;
@@ -298,7 +284,7 @@ hashattn_status hashattn_score_topk(hashattn_ctx* ctx, const uint32_t* q_codes, 
         return fail(ctx, HASHATTN_INVALID_ARG, "score_topk: 4-byte alignment required");
     if (k_max < 1) return fail(ctx, HASHATTN_INVALID_ARG, "score_topk: k_max %d < 1", k_max);
     if (k_max > ctx->cfg.max_k) return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "score_topk: k_max %d exceeds max_k %lld", k_max, (long long)ctx->cfg.max_k);
-    const ha::TopkScratch sc{ctx->unit_cum, ctx->ghist, ctx->tickets, ctx->units_pitch};
+    const ha::TopkScratch sc{ctx->blk_cum, ctx->unit_cum, ctx->blocks_pitch};
     const int unit = pick_unit_tokens(ctx, batch, cache->max_seq_len);
     const hipError_t e = ha::launch_score_topk(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group, q_codes, batch,
                                                ctx->cfg.n_q_heads, k_per_seq, k_max, cache->max_seq_len, unit, sc,

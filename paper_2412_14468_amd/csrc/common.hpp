@@ -8,9 +8,11 @@ namespace ha {
 constexpr int kHeadDim = 128;     // bf16 elements per K/V row (256 bytes)
 constexpr int kBits = 32;         // signature width
 constexpr int kBins = 33;         // Hamming similarity takes values 0..32
+constexpr int kCumRow = 34;       // row of cumulative score counts: bins 0..32 and a zero slot
 constexpr int kPage = 16;         // tokens per page in the paged layout
 constexpr int kWave = 64;
-constexpr int kMaxScanUnits = 960;  // most units per sequence: every block sums two table rows over the units before it
+constexpr int kTopkWavesPerBlock = 16;   // SCORE/TOPK: units (waves) per block
+constexpr int kMaxTopkBlocks = 128;      // SCORE/TOPK: most blocks per sequence (every block sums the per-block tables)
 constexpr int kPartStride = 132;  // floats per split partial: acc[128], m, l, pad
 
 // Plain view of the caller's KV cache, passed to kernels by value.

@@ -14,10 +14,9 @@ struct MlpView {
 };
 
 struct TopkScratch {
-    uint16_t* unit_cum;    // [B][Hq][33][units_pitch]: per unit, #{score >= s}
-    int32_t* ghist;        // [B][Hq][33]: per head score counts; zero between calls
-    int32_t* tickets;      // [B][Hkv]: finished-block counters of topk_select; zero between calls
-    int32_t units_pitch;
+    int32_t* blk_cum;      // [B][Hq][blocks_pitch][34]: per block of 16 units, #{score >= s}
+    uint16_t* unit_cum;    // [B][Hq][blocks_pitch * 16][34]: the same per unit
+    int32_t blocks_pitch;
 };
 
 hipError_t launch_encode_query(const MlpView& phi, const uint16_t* q, int batch, int n_heads,
