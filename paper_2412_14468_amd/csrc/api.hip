@@ -125,9 +125,9 @@ int pick_unit_tokens(const hashattn_ctx* ctx, int batch, int max_seq_len)
     const int64_t lanes = (int64_t)batch * ctx->cfg.n_kv_heads;
     int unit = kMinUnit;
     auto blocks = [&](int u) { return (max_seq_len + (int64_t)u * ha::kTopkWavesPerBlock - 1) / ((int64_t)u * ha::kTopkWavesPerBlock); };
-    // aim for at most about 8192 waves over the whole grid, never more blocks than the scratch pitch
-    while (unit < kMaxUnit &&
-           (lanes * ((max_seq_len + unit - 1) / unit) > 8192 || blocks(unit) > ctx->blocks_pitch))
+    // a 16-wave block fills a CU: prefer one round of blocks over the 256 CUs, never more blocks
+    // per sequence than the scratch pitch
+    while (unit < kMaxUnit && (lanes * blocks(unit) > 256 || blocks(unit) > ctx->blocks_pitch))
         unit *= 2;
     return unit;
 }

@@ -130,12 +130,13 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
     }
 }
 
-// 16-bit mask of one lane's tokens of a chunk (bit it * 4 + e) whose Hamming distance to qc is <= lim.
+// Mask of one lane's tokens of a chunk (bit it * 4 + e, it < NIT) whose Hamming distance to qc is <= lim.
+template <int NIT>
 __device__ __forceinline__ unsigned near_mask(const uint4 (&cw)[4], uint32_t qc, int lim)
 {
     unsigned m = 0;
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
+    for (int it = 0; it < NIT; ++it) {
         const uint32_t w[4] = {cw[it].x, cw[it].y, cw[it].z, cw[it].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) m |= (unsigned)((int)__popc(w[e] ^ qc) <= lim) << (it * 4 + e);
@@ -143,11 +144,12 @@ __device__ __forceinline__ unsigned near_mask(const uint4 (&cw)[4], uint32_t qc,
     return m;
 }
 
+template <int NIT>
 __device__ __forceinline__ unsigned equal_mask(const uint4 (&cw)[4], uint32_t qc, int dist)
 {
     unsigned m = 0;
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
+    for (int it = 0; it < NIT; ++it) {
         const uint32_t w[4] = {cw[it].x, cw[it].y, cw[it].z, cw[it].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) m |= (unsigned)((int)__popc(w[e] ^ qc) == dist) << (it * 4 + e);
@@ -155,21 +157,89 @@ __device__ __forceinline__ unsigned equal_mask(const uint4 (&cw)[4], uint32_t qc
     return m;
 }
 
-// Lane-exclusive prefix counts of the four 4-bit groups of m over the wave, and the wave totals.
-// Two 16-bit fields per register, so two scans serve the four groups (a group holds at most 256).
+// Lane-exclusive prefix counts of the 4-bit groups of m (NIT of them) over the wave, and the wave totals.
+// Two 16-bit fields per register, so one scan serves two groups (a group holds at most 256).
+template <int NIT>
 __device__ __forceinline__ void group_ranks(unsigned m, int (&excl)[4], int (&total)[4])
 {
-    const int c0 = __popc(m & 0xfu), c1 = __popc(m & 0xf0u), c2 = __popc(m & 0xf00u), c3 = __popc(m & 0xf000u);
-    const int i01 = wave_incl_scan_i32(c0 | (c1 << 16)), i23 = wave_incl_scan_i32(c2 | (c3 << 16));
-    const int t01 = __builtin_amdgcn_readlane(i01, 63), t23 = __builtin_amdgcn_readlane(i23, 63);
+    const int c0 = __popc(m & 0xfu), c1 = __popc(m & 0xf0u);
+    const int i01 = wave_incl_scan_i32(c0 | (c1 << 16));
+    const int t01 = __builtin_amdgcn_readlane(i01, 63);
     excl[0] = (i01 & 0xffff) - c0;
     excl[1] = (int)((unsigned)i01 >> 16) - c1;
-    excl[2] = (i23 & 0xffff) - c2;
-    excl[3] = (int)((unsigned)i23 >> 16) - c3;
     total[0] = t01 & 0xffff;
     total[1] = (int)((unsigned)t01 >> 16);
-    total[2] = t23 & 0xffff;
-    total[3] = (int)((unsigned)t23 >> 16);
+    excl[2] = excl[3] = total[2] = total[3] = 0;
+    if constexpr (NIT > 2) {
+        const int c2 = __popc(m & 0xf00u), c3 = __popc(m & 0xf000u);
+        const int i23 = wave_incl_scan_i32(c2 | (c3 << 16));
+        const int t23 = __builtin_amdgcn_readlane(i23, 63);
+        excl[2] = (i23 & 0xffff) - c2;
+        excl[3] = (int)((unsigned)i23 >> 16) - c3;
+        total[2] = t23 & 0xffff;
+        total[3] = (int)((unsigned)t23 >> 16);
+    }
+}
+
+// Compaction of one chunk (NIT groups of 256 tokens starting at `base`) of one wave for its G heads.
+template <int G, int NIT>
+__device__ __forceinline__ void compact_chunk(const uint4 (&cw)[4], int base, int t_end, int lane,
+                                              const uint32_t (&qc)[G], const int (&lim)[G], const int (&quota)[G],
+                                              int (&pos)[G], int (&ties_seen)[G], int32_t* __restrict__ idx0,
+                                              int k_max)
+{
+    unsigned valid = 0xffffu;                             // tokens of this lane that exist
+    if (base + NIT * 4 * kWave > t_end) {                 // ragged last chunk (uniform over the wave)
+        valid = 0;
+#pragma unroll
+        for (int it = 0; it < NIT; ++it)
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+                valid |= (unsigned)(base + it * 4 * kWave + lane * 4 + e < t_end) << (it * 4 + e);
+    }
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        unsigned m = near_mask<NIT>(cw, qc[j], lim[j]) & valid;
+        if (quota[j] != kAllTies && quota[j] != 0) {
+            // the unit where the tie quota runs out: ties are ranked in token order
+            const unsigned ties = equal_mask<NIT>(cw, qc[j], lim[j] + 1) & valid;
+            int ex[4], tt[4];
+            group_ranks<NIT>(ties, ex, tt);
+            int before_group = ties_seen[j];
+#pragma unroll
+            for (int it = 0; it < NIT; ++it) {
+                int rank = before_group + ex[it];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const unsigned bit = 1u << (it * 4 + e);
+                    if (ties & bit) {
+                        if (rank < quota[j]) m |= bit;
+                        ++rank;
+                    }
+                }
+                before_group += tt[it];
+            }
+            ties_seen[j] = before_group;
+        }
+        int ex[4], tt[4];
+        group_ranks<NIT>(m, ex, tt);
+        int32_t* out = idx0 + (int64_t)j * k_max;
+        int group_start = pos[j];
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            int rank = group_start + ex[it];
+            const int t0 = base + it * 4 * kWave + lane * 4;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                if (m & (1u << (it * 4 + e))) {
+                    if (rank < k_max) out[rank] = t0 + e;
+                    ++rank;
+                }
+            }
+            group_start += tt[it];
+        }
+        pos[j] = group_start;
+    }
 }
 
 template <int G, bool PAGED>
@@ -293,58 +363,14 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
     }
     for (int base = (int)t_begin; base < t_end; base += kChunk) {
         if (base != (int)t_begin) load_chunk<PAGED>(c, b, kvh, base, t_end, lane, cw);
-        unsigned valid = 0xffffu;                             // tokens of this lane that exist
-        if (base + kChunk > t_end) {                          // ragged last chunk (uniform over the wave)
-            valid = 0;
-#pragma unroll
-            for (int it = 0; it < 4; ++it)
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    valid |= (unsigned)(base + it * 4 * kWave + lane * 4 + e < t_end) << (it * 4 + e);
-        }
-#pragma unroll
-        for (int j = 0; j < G; ++j) {
-            unsigned m = near_mask(cw, qc[j], lim[j]) & valid;
-            if (quota[j] != kAllTies && quota[j] != 0) {
-                // the unit where the tie quota runs out: ties are ranked in token order
-                const unsigned ties = equal_mask(cw, qc[j], lim[j] + 1) & valid;
-                int ex[4], tt[4];
-                group_ranks(ties, ex, tt);
-                int before_group = ties_seen[j];
-#pragma unroll
-                for (int it = 0; it < 4; ++it) {
-                    int rank = before_group + ex[it];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) {
-                        const unsigned bit = 1u << (it * 4 + e);
-                        if (ties & bit) {
-                            if (rank < quota[j]) m |= bit;
-                            ++rank;
-                        }
-                    }
-                    before_group += tt[it];
-                }
-                ties_seen[j] = before_group;
-            }
-            int ex[4], tt[4];
-            group_ranks(m, ex, tt);
-            int32_t* out = idx + (bh0 + j) * k_max;
-            int group_start = pos[j];
-#pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                int rank = group_start + ex[it];
-                const int t0 = base + it * 4 * kWave + lane * 4;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (m & (1u << (it * 4 + e))) {
-                        if (rank < k_max) out[rank] = t0 + e;
-                        ++rank;
-                    }
-                }
-                group_start += tt[it];
-            }
-            pos[j] = group_start;
-        }
+        const int groups = (min(t_end - base, kChunk) + 4 * kWave - 1) / (4 * kWave);     // uniform over the wave
+        int32_t* idx0 = idx + bh0 * k_max;
+        if (groups == 1)
+            compact_chunk<G, 1>(cw, base, t_end, lane, qc, lim, quota, pos, ties_seen, idx0, k_max);
+        else if (groups == 2)
+            compact_chunk<G, 2>(cw, base, t_end, lane, qc, lim, quota, pos, ties_seen, idx0, k_max);
+        else
+            compact_chunk<G, 4>(cw, base, t_end, lane, qc, lim, quota, pos, ties_seen, idx0, k_max);
     }
 }
 
