@@ -68,41 +68,10 @@ def device_layer_from_host(L, torch, ha):
 
 
 def device_layer_synthetic(cfg, seed, torch):
-    """Other ring layers: same recipe drawn on the device (K, V, Q ~ N(0,1) in bf16, planted keys
-    4 q/|q| + 0.1 N(0,1) at 64 positions per query head, U(-1/sqrt(fan_in), 1/sqrt(fan_in)) weights)."""
-    from paper_2412_14468_amd.runner import LayerState
-    dev = "cuda:0"
-    g = torch.Generator(device=dev)
-    g.manual_seed(seed)
-    B, Hq, Hkv, d, N = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.context
-    q = torch.randn((B, Hq, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
-    k = torch.empty((B, Hkv, N, d), device=dev, dtype=torch.bfloat16)
-    v = torch.empty((B, Hkv, N, d), device=dev, dtype=torch.bfloat16)
-    for t in (k, v):
-        for b in range(B):
-            for h in range(Hkv):
-                t[b, h] = torch.randn((N, d), generator=g, device=dev, dtype=torch.float32).to(torch.bfloat16)
-    grp = Hq // Hkv
-    if cfg.planted > 0:
-        for b in range(B):
-            for hk in range(Hkv):
-                pos = torch.randperm(N, generator=g, device=dev)[:cfg.planted * grp]
-                for j in range(grp):
-                    qv = q[b, hk * grp + j].float()
-                    rows = 4.0 * qv / qv.norm() + 0.1 * torch.randn((cfg.planted, d), generator=g, device=dev)
-                    k[b, hk, pos[j * cfg.planted:(j + 1) * cfg.planted]] = rows.to(torch.bfloat16)
-    dims = cfg.mlp_dims
-
-    def weights(n_heads):
-        out = []
-        for l in range(len(dims) - 1):
-            bound = 1.0 / math.sqrt(dims[l])
-            w = (torch.rand((n_heads, dims[l], dims[l + 1]), generator=g, device=dev) * 2 - 1) * bound
-            out.append(w.contiguous())
-        return out
-
-    seq_lens = torch.full((B,), N, dtype=torch.int32, device=dev)
-    return LayerState(q, k, v, seq_lens, N, weights(Hq), weights(Hkv), None, cfg.k)
+    """Other ring layers: the same recipe drawn on the device."""
+    import workloads as W
+    from paper_2412_14468_amd.runner import layer_from_tensors
+    return layer_from_tensors(W.device_tensors(cfg, seed))
 
 
 def time_region(torch, fn, reps):

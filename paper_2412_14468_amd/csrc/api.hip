@@ -5,6 +5,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 
@@ -139,12 +140,15 @@ void pick_splits(const hashattn_ctx* ctx, int64_t lanes, int64_t total, int batc
     int64_t cap = ctx->part_floats / ((int64_t)batch * ctx->cfg.n_q_heads * ha::kPartStride);
     if (cap > kMaxSplits) cap = kMaxSplits;
     if (cap < 1) cap = 1;
-    int64_t want = (2048 + lanes - 1) / lanes;                 // about 8 blocks per CU over the grid
+    int64_t target = 2048, min_chunk = 64;
+    if (const char* e = getenv("HA_BLOCKS_TARGET")) target = atoll(e);
+    if (const char* e = getenv("HA_MIN_CHUNK")) min_chunk = atoll(e);
+    int64_t want = (target + lanes - 1) / lanes;
     if (want > cap) want = cap;
     if (want < 1) want = 1;
     int64_t c = (total + want - 1) / want;
     c = (c + 63) / 64 * 64;                                    // whole 64-row iterations
-    if (c < 64) c = 64;
+    if (c < min_chunk) c = min_chunk;
     int64_t s = (total + c - 1) / c;
     if (s < 1) s = 1;
     while (s > cap) { c *= 2; s = (total + c - 1) / c; }

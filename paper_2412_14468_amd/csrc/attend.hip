@@ -4,7 +4,10 @@
 // is cut into splits; a block keeps an online-softmax state (running max m,
 // running sum l, fp32 accumulator) per 16-lane row group, merges its 16 states
 // through LDS and writes one partial (acc[128], m, l).  A second, small kernel
-// merges the partials of a head and rounds to bf16.  (Merging in the block that
+// merges the partials of a head and rounds to bf16.  Short lists with many heads
+// skip the split: one 16-wave block per head writes the output itself (with few
+// heads that is slower: one CU pulls only about 30 GB/s of scattered rows).
+// (Merging in the block that
 // finishes last was measured and dropped: the device-scope release/acquire it
 // needs writes back and invalidates the XCD's whole L2 in every block, which
 // cost far more than the extra launch.)
@@ -24,8 +27,8 @@ namespace ha {
 
 namespace {
 
-constexpr int kRowsPerIter = 64;   // rows a block consumes per loop iteration
-constexpr int kSlots = 16;         // row groups per block (4 waves x 4 groups)
+constexpr int kDirectRows = 1024;  // lists up to this long can be handled by one 16-wave block per head ...
+constexpr int kDirectMinHeads = 128;   // ... when there are at least this many (sequence, head) pairs
 constexpr int kMaxSplits = 256;
 constexpr float kNegInf = -INFINITY;
 
@@ -67,24 +70,51 @@ __device__ __forceinline__ float dot8_row16(const float (&qf)[8], const uint4& k
     return row16_sum(d);
 }
 
-// Merge the 16 per-group states of a block (st: [kSlots][kPartStride] floats in LDS, already
-// filled and synchronised) and write the block's partial.
+// Merge the SLOTS per-group states of a block (st: [SLOTS][kPartStride] floats in LDS, already
+// filled and synchronised).  Threads 0..127 get their channel's weighted sum, thread 129 the weighted
+// sum of l; M is the block's running max (all in the returned struct, valid for tid < 130).
+struct BlockState { float sum, M; };
+
+template <int SLOTS>
+__device__ __forceinline__ BlockState merge_slots(const float* st)
+{
+    const int tid = threadIdx.x;
+    BlockState r{0.f, kNegInf};
+    if (tid < kHeadDim + 2) {
+#pragma unroll 8
+        for (int s = 0; s < SLOTS; ++s) r.M = fmaxf(r.M, st[s * kPartStride + kHeadDim]);
+        const float Ms = (r.M == kNegInf) ? 0.f : r.M;
+        const int col = tid < kHeadDim ? tid : kHeadDim + 1;      // channel, or the l column
+#pragma unroll 8
+        for (int s = 0; s < SLOTS; ++s)
+            r.sum += st[s * kPartStride + col] * exp2f(st[s * kPartStride + kHeadDim] - Ms);
+    }
+    return r;
+}
+
+// Write the block's partial (acc[128], m, l).
+template <int SLOTS>
 __device__ __forceinline__ void write_partial(const float* st, float* part)
 {
     const int tid = threadIdx.x;
-    if (tid < kHeadDim + 2) {
-        float M = kNegInf;
-#pragma unroll
-        for (int s = 0; s < kSlots; ++s) M = fmaxf(M, st[s * kPartStride + kHeadDim]);
-        const float Ms = (M == kNegInf) ? 0.f : M;
-        float sum = 0.f;
-        const int col = tid < kHeadDim ? tid : kHeadDim + 1;      // channel, or the l column
-#pragma unroll
-        for (int s = 0; s < kSlots; ++s)
-            sum += st[s * kPartStride + col] * exp2f(st[s * kPartStride + kHeadDim] - Ms);
-        if (tid < kHeadDim) part[tid] = sum;
-        else if (tid == kHeadDim) part[kHeadDim] = M;
-        else part[kHeadDim + 1] = sum;
+    const BlockState r = merge_slots<SLOTS>(st);
+    if (tid < kHeadDim) part[tid] = r.sum;
+    else if (tid == kHeadDim) part[kHeadDim] = r.M;
+    else if (tid == kHeadDim + 1) part[kHeadDim + 1] = r.sum;
+}
+
+// The block holds the whole token list of its head: normalise and round to bf16 directly.
+// red: one float of LDS outside st.
+template <int SLOTS>
+__device__ __forceinline__ void write_output(const float* st, float* red, uint16_t* out)
+{
+    const int tid = threadIdx.x;
+    const BlockState r = merge_slots<SLOTS>(st);
+    if (tid == kHeadDim + 1) *red = r.sum;
+    __syncthreads();
+    if (tid < kHeadDim) {
+        const float den = *red;
+        out[tid] = (uint16_t)f32_to_bf16(den > 0.f ? r.sum / den : 0.f);
     }
 }
 
@@ -136,17 +166,23 @@ __device__ __forceinline__ void merge_partials_block(const float* __restrict__ p
     }
 }
 
-template <bool PAGED>
-__global__ __launch_bounds__(256) void gather_attend_kernel(KvView c, const uint16_t* __restrict__ q,
-                                                            const int32_t* __restrict__ idx,
-                                                            const int32_t* __restrict__ count,
-                                                            int n_q_heads, int group, int k_max, int chunk,
-                                                            int n_splits, float scale_log2e,
-                                                            float* __restrict__ part)
+// WAVES waves per block; every 16-lane group ("slot") owns rows slot, slot + SLOTS, ... of the block's
+// share of the list.  DIRECT: one block per (sequence, head) takes the whole list and writes the bf16
+// output itself (short lists: no partials, no second launch).
+template <bool PAGED, int WAVES, bool DIRECT>
+__global__ __launch_bounds__(WAVES * 64) void gather_attend_kernel(KvView c, const uint16_t* __restrict__ q,
+                                                                   const int32_t* __restrict__ idx,
+                                                                   const int32_t* __restrict__ count,
+                                                                   int n_q_heads, int group, int k_max, int chunk,
+                                                                   int n_splits, float scale_log2e,
+                                                                   float* __restrict__ part,
+                                                                   uint16_t* __restrict__ out)
 {
+    constexpr int kSlots = WAVES * 4, kRowsPerIter = kSlots * 4;
     __shared__ float st[kSlots * kPartStride];
+    __shared__ float red;
     const int tid = threadIdx.x, lane = tid & 63, sub = lane & 15;
-    const int slot = tid >> 4;                       // 0..15
+    const int slot = tid >> 4;                       // 0..kSlots-1
     const int split = blockIdx.x, hq = blockIdx.y, b = blockIdx.z, kvh = hq / group;
     const int64_t bh = (int64_t)b * n_q_heads + hq;
     const int32_t* my_idx = idx + bh * k_max;
@@ -159,8 +195,11 @@ __global__ __launch_bounds__(256) void gather_attend_kernel(KvView c, const uint
     for (int i = 0; i < 4; ++i) tok[i] = my_idx[min(begin + i * kSlots + slot, k_max - 1)];
     const int cnt = min(count[bh], k_max);
     const uint4 qraw = *reinterpret_cast<const uint4*>(q + bh * kHeadDim + sub * 8);
-    if (begin >= cnt) return;                        // the merge kernel skips unused splits
-    const int end = min(begin + chunk, cnt);
+    if (begin >= cnt) {
+        if (DIRECT && tid < kHeadDim) out[bh * kHeadDim + tid] = 0;   // empty list: zero row
+        return;                                      // split mode: the merge kernel skips unused splits
+    }
+    const int end = DIRECT ? cnt : min(begin + chunk, cnt);
 
     float qf[8];
     unpack8(qraw, qf);
@@ -219,7 +258,8 @@ __global__ __launch_bounds__(256) void gather_attend_kernel(KvView c, const uint
     for (int e = 0; e < 8; ++e) mine[sub * 8 + e] = acc[e];
     if (sub == 0) { mine[kHeadDim] = m; mine[kHeadDim + 1] = l; }
     __syncthreads();
-    write_partial(st, part + (bh * n_splits + split) * kPartStride);
+    if constexpr (DIRECT) write_output<kSlots>(st, &red, out + bh * kHeadDim);
+    else write_partial<kSlots>(st, part + (bh * n_splits + split) * kPartStride);
 }
 
 // Dense decode: the block walks a contiguous token range of one KV head and serves
@@ -229,6 +269,7 @@ __global__ __launch_bounds__(256) void dense_attend_kernel(KvView c, const uint1
                                                            int n_q_heads, int n_cap, int chunk, int n_splits,
                                                            float scale_log2e, float* __restrict__ part)
 {
+    constexpr int kSlots = 16, kRowsPerIter = 64;    // 4 waves x 4 row groups, 4 rows per group and iteration
     __shared__ float st[kSlots * kPartStride];
     const int tid = threadIdx.x, lane = tid & 63, sub = lane & 15;
     const int slot = tid >> 4;
@@ -302,7 +343,7 @@ __global__ __launch_bounds__(256) void dense_attend_kernel(KvView c, const uint1
         for (int e = 0; e < 8; ++e) mine[sub * 8 + e] = acc[j][e];
         if (sub == 0) { mine[kHeadDim] = m[j]; mine[kHeadDim + 1] = l[j]; }
         __syncthreads();
-        write_partial(st, part + ((bh0 + j) * n_splits + split) * kPartStride);
+        write_partial<kSlots>(st, part + ((bh0 + j) * n_splits + split) * kPartStride);
     }
 }
 
@@ -331,13 +372,24 @@ hipError_t launch_gather_attend(const KvView& kv, bool paged, int group, const u
                                 int k_max, int chunk, int n_splits, float scale, float* part,
                                 uint16_t* out, hipStream_t stream)
 {
+    // short lists and enough heads to fill the chip: one block per head, no partials
+    if (k_max <= kDirectRows && (int64_t)batch * n_q_heads >= kDirectMinHeads) {
+        const dim3 grid(1, n_q_heads, batch), block(1024);
+        if (paged)
+            gather_attend_kernel<true, 16, true><<<grid, block, 0, stream>>>(kv, q, idx, count, n_q_heads, group, k_max,
+                                                                             k_max, 1, scale * kLog2e, part, out);
+        else
+            gather_attend_kernel<false, 16, true><<<grid, block, 0, stream>>>(kv, q, idx, count, n_q_heads, group, k_max,
+                                                                              k_max, 1, scale * kLog2e, part, out);
+        return hipGetLastError();
+    }
     const dim3 grid(n_splits, n_q_heads, batch), block(256);
     if (paged)
-        gather_attend_kernel<true><<<grid, block, 0, stream>>>(kv, q, idx, count, n_q_heads, group, k_max, chunk,
-                                                               n_splits, scale * kLog2e, part);
+        gather_attend_kernel<true, 4, false><<<grid, block, 0, stream>>>(kv, q, idx, count, n_q_heads, group, k_max, chunk,
+                                                                         n_splits, scale * kLog2e, part, out);
     else
-        gather_attend_kernel<false><<<grid, block, 0, stream>>>(kv, q, idx, count, n_q_heads, group, k_max, chunk,
-                                                                n_splits, scale * kLog2e, part);
+        gather_attend_kernel<false, 4, false><<<grid, block, 0, stream>>>(kv, q, idx, count, n_q_heads, group, k_max, chunk,
+                                                                          n_splits, scale * kLog2e, part, out);
     merge_partials_kernel<true><<<dim3(n_q_heads, batch), block, 0, stream>>>(part, count, k_max, n_q_heads, chunk,
                                                                               n_splits, out);
     return hipGetLastError();

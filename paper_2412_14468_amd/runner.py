@@ -38,6 +38,14 @@ class LayerState:
         self.scale = 1.0 / math.sqrt(self.d)
 
 
+def layer_from_tensors(t: dict) -> LayerState:
+    """LayerState over a dict of device tensors as made by workloads.device_tensors."""
+    uniform_k = bool((t["k_per_seq_host"] == t["k_per_seq_host"][0]).all())
+    return LayerState(t["q"], t["k"], t["v"], t["seq_lens"], int(t["seq_lens_host"].max()), t["w_q"], t["w_kv"],
+                      None if uniform_k else t["k_per_seq"], int(t["k_per_seq_host"].max()),
+                      page_table=t["page_table"], k_new=t["k_new"], v_new=t["v_new"])
+
+
 def build_key_codes(ctx: Context, s: LayerState) -> None:
     """Prefill-side: (re)build the whole key-code store from the cached keys."""
     ctx.hashattn_encode_keys(s.phi_kv, None, None, s.B, max(s.cache.max_seq_len, 1), s.cache)

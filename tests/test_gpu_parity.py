@@ -268,6 +268,15 @@ def test_llama_shape_ragged_batch():
     run_whole_step(L)
 
 
+def test_many_heads_short_lists_single_block_path():
+    """k <= 1024 with at least 128 (sequence, head) pairs: GATHER-ATT runs one block per head."""
+    cfg = W.scaled(W.c1(), context=3001, k=97, batch=5, planted=8)
+    L = W.make_layer(cfg, seed=42)
+    L.seq_lens[:] = [3001, 0, 17, 2048, 96]
+    L.k_per_seq[:] = [97, 97, 97, 1, 96]
+    run_whole_step(L)
+
+
 def test_c1_full_size():
     """Llama-3.1-8B-shaped layer, N = 32768, k = 1024: every head against the oracle."""
     L = W.make_layer(W.c1())

@@ -242,6 +242,98 @@ def make_layer(cfg: Config, seed: Optional[int] = None) -> Layer:
 
 
 # --------------------------------------------------------------------------
+# the same recipe drawn on the device (large configurations: drawing GiB of normals with numpy
+# would take minutes).  Inputs only: a seeded torch generator, no arithmetic of the method.
+# --------------------------------------------------------------------------
+def device_tensors(cfg: Config, seed: int, device: str = "cuda:0", extra_rows: int = 0) -> dict:
+    """K, V, Q ~ N(0,1) in bf16, planted keys 4 q/|q| + 0.1 N(0,1), U(-1/sqrt(fan_in), 1/sqrt(fan_in))
+    fp32 weights, as torch tensors on `device`.  Contiguous or paged layout as cfg says; for append
+    configs the cache holds N-1 rows and k_new/v_new carry the N-th."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed(seed)
+    B, Hq, Hkv, d = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
+    grp = Hq // Hkv
+    host_rng = np.random.Generator(np.random.PCG64(np.random.SeedSequence(seed)))
+    if cfg.mixed_lengths is not None:
+        final_lens = draw_lengths(host_rng, B, *cfg.mixed_lengths)
+    else:
+        final_lens = np.full(B, cfg.context, dtype=np.int32)
+    seq_lens = final_lens - (1 if cfg.append else 0)
+    if cfg.k_divisor > 0:
+        k_per_seq = ((final_lens + cfg.k_divisor - 1) // cfg.k_divisor).astype(np.int32)
+    else:
+        k_per_seq = np.full(B, cfg.k, dtype=np.int32)
+
+    def normal_bf16(shape):
+        return torch.randn(shape, generator=g, device=device, dtype=torch.float32).to(torch.bfloat16)
+
+    q = normal_bf16((B, Hq, d))
+    page_table = None
+    if cfg.page_size > 0:
+        ps = cfg.page_size
+        pages_per_seq = (final_lens + ps - 1) // ps
+        max_pages, total_pages = int(pages_per_seq.max()), int(pages_per_seq.sum())
+        perm = host_rng.permutation(total_pages).astype(np.int32)
+        table = np.full((B, max_pages), -1, dtype=np.int32)
+        off = 0
+        for b in range(B):
+            table[b, :pages_per_seq[b]] = perm[off:off + pages_per_seq[b]]
+            off += int(pages_per_seq[b])
+        page_table = torch.from_numpy(table).to(device)
+        k = torch.empty((total_pages, Hkv, ps, d), device=device, dtype=torch.bfloat16)
+        v = torch.empty_like(k)
+        step = 4096
+        for t in (k, v):
+            for p0 in range(0, total_pages, step):
+                p1 = min(total_pages, p0 + step)
+                t[p0:p1] = normal_bf16((p1 - p0, Hkv, ps, d))
+        n_max = max_pages * ps
+    else:
+        n_max = int(final_lens.max()) + extra_rows
+        n_max += (-n_max) % 4
+        k = torch.empty((B, Hkv, n_max, d), device=device, dtype=torch.bfloat16)
+        v = torch.empty_like(k)
+        for t in (k, v):
+            for b in range(B):
+                for h in range(Hkv):
+                    t[b, h] = normal_bf16((n_max, d))
+    if cfg.planted > 0:
+        for b in range(B):
+            n_b = int(seq_lens[b])
+            per_kv = min(cfg.planted * grp, n_b)
+            for hk in range(Hkv):
+                pos = torch.randperm(n_b, generator=g, device=device)[:per_kv]
+                for j in range(grp):
+                    mine = pos[j * cfg.planted:(j + 1) * cfg.planted]
+                    if mine.numel() == 0:
+                        continue
+                    qv = q[b, hk * grp + j].float()
+                    rows = 4.0 * qv / qv.norm() + 0.1 * torch.randn((mine.numel(), d), generator=g, device=device)
+                    if page_table is None:
+                        k[b, hk, mine] = rows.to(torch.bfloat16)
+                    else:
+                        k[page_table[b, mine // cfg.page_size].long(), hk, mine % cfg.page_size] = rows.to(torch.bfloat16)
+
+    def weights(n_heads):
+        out = []
+        for l in range(len(cfg.mlp_dims) - 1):
+            bound = 1.0 / math.sqrt(cfg.mlp_dims[l])
+            w = (torch.rand((n_heads, cfg.mlp_dims[l], cfg.mlp_dims[l + 1]), generator=g, device=device) * 2 - 1) * bound
+            out.append(w.contiguous())
+        return out
+
+    out = dict(q=q, k=k, v=v, seq_lens_host=seq_lens.astype(np.int32), k_per_seq_host=k_per_seq,
+               seq_lens=torch.from_numpy(seq_lens.astype(np.int32)).to(device),
+               k_per_seq=torch.from_numpy(k_per_seq).to(device), page_table=page_table, n_max=n_max,
+               w_q=weights(Hq), w_kv=weights(Hkv), k_new=None, v_new=None)
+    if cfg.append:
+        out["k_new"] = normal_bf16((B, Hkv, 1, d))
+        out["v_new"] = normal_bf16((B, Hkv, 1, d))
+    return out
+
+
+# --------------------------------------------------------------------------
 # byte accounting used by the benchmark report (sizes only, no arithmetic of
 # the method): key codes + gathered K/V rows + Q and O
 # --------------------------------------------------------------------------
