@@ -35,26 +35,32 @@ def parse_args():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=640)
     ap.add_argument("--warmup", type=int, default=64)
-    ap.add_argument("--workload", default="C1", choices=["C1", "C1-128K", "C3", "C3-16x"],
+    ap.add_argument("--workload", default="C1", choices=list(WORKLOADS),
                     help="C1 = Llama-3.1-8B layer, B=1, N=32768, k=1024 (the headline configuration)")
     ap.add_argument("--ring", type=int, default=0, help="distinct layers walked by the steps (0 = per workload)")
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     return ap.parse_args()
+
+
+# workload name -> (config factory, ring length).  The ring is sized past the 256 MB Infinity Cache.
+WORKLOADS = {
+    "C1": (lambda W: W.c1(), 32),
+    "C1-128K": (lambda W: W.scaled(W.c1(context=131072), name="C1-128K"), 8),
+    "C2": (lambda W: W.c2(), 2),
+    "C3": (lambda W: W.c3(), 4),
+    "C3-16x": (lambda W: W.scaled(W.c3(k=32768), name="C3-16x"), 4),
+    "C4": (lambda W: W.c4(), 2),
+}
 
 
 def workload_config(name):
     import workloads as W
-    if name == "C1":
-        return W.c1(), 32
-    if name == "C1-128K":
-        return W.scaled(W.c1(context=131072), name="C1-128K"), 8
-    if name == "C3":
-        return W.c3(), 4
-    if name == "C3-16x":
-        return W.scaled(W.c3(k=32768), name="C3-16x"), 4
-    raise ValueError(name)
+    make, ring = WORKLOADS[name]
+    return make(W), ring
 
 
 def device_layer_from_host(L, torch, ha):
@@ -68,10 +74,28 @@ def device_layer_from_host(L, torch, ha):
 
 
 def device_layer_synthetic(cfg, seed, torch):
-    """Other ring layers: the same recipe drawn on the device."""
+    """Ring layers drawn on the device by the same recipe (workloads.device_tensors)."""
     import workloads as W
     from paper_2412_14468_amd.runner import layer_from_tensors
-    return layer_from_tensors(W.device_tensors(cfg, seed))
+    t = W.device_tensors(cfg, seed)
+    s = layer_from_tensors(t)
+    s.lens_host, s.k_host = t["seq_lens_host"], t["k_per_seq_host"]
+    return s
+
+
+def describe_lengths(v):
+    return str(v[0]) if min(v) == max(v) else f"{min(v)}..{max(v)} (sum {sum(v)})"
+
+
+def stored_traffic(workload):
+    """HBM bytes per GATHER-ATT launch from the committed rocprofv3 --pmc summary, if there is one
+    (counters cannot be read from inside this process)."""
+    path = os.path.join(ROOT, "profiles", "gather_attend_traffic.json")
+    try:
+        with open(path) as f:
+            return json.load(f).get(workload)
+    except (OSError, ValueError):
+        return None
 
 
 def time_region(torch, fn, reps):
@@ -126,22 +150,43 @@ def main():
     ha.load()
     cfg, ring_default = workload_config(args.workload)
     ring = args.ring or ring_default
-    B, Hq, Hkv, d, N, k = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.context, cfg.k
+    B, Hq, Hkv, d, N = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.context
+    host_layer0 = args.workload == "C1" and not args.no_cpu_baseline      # numpy layer 0 feeds the oracle too
 
     t_setup = time.perf_counter()
-    L0 = W.make_layer(cfg)
-    layers = [device_layer_from_host(L0, torch, ha)]
-    for i in range(1, ring):
-        layers.append(device_layer_synthetic(cfg, W.BASE_SEED + 1000 * cfg.index + i, torch))
-    ctx = ha.Context(Hq, Hkv, B, N, k)
+    layers = []
+    L0 = None
+    if host_layer0:
+        L0 = W.make_layer(cfg)
+        s0 = device_layer_from_host(L0, torch, ha)
+        s0.lens_host, s0.k_host = L0.seq_lens.copy(), L0.k_per_seq.copy()
+        layers.append(s0)
+    while len(layers) < ring:
+        layers.append(device_layer_synthetic(cfg, W.BASE_SEED + 1000 * cfg.index + len(layers), torch))
+    n_cap = max(int(s.k.shape[2]) if s.page_table is None else int(s.page_table.shape[1]) * cfg.page_size for s in layers)
+    k_max = max(s.k_max for s in layers)
+    ctx = ha.Context(Hq, Hkv, B, n_cap, k_max, page_size=cfg.page_size)
     for s in layers:
         runner.build_key_codes(ctx, s)
+        s.lens0_dev = s.seq_lens.clone()
+        s.max_len0 = s.cache.max_seq_len
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
+    if args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+        torch.empty_like(src).copy_(src)
+        torch.cuda.synchronize()
+        del src
+
+    def one_step(s):
+        if cfg.append:                       # every step appends to a cache that holds N - 1 tokens
+            s.seq_lens.copy_(s.lens0_dev)
+            s.cache.max_seq_len = s.max_len0
+        runner.decode_step(ctx, s, append=cfg.append)
 
     def sweep(n_steps, start=0):
         for i in range(n_steps):
-            runner.decode_step(ctx, layers[(start + i) % ring])
+            one_step(layers[(start + i) % ring])
 
     # ---- whole-step timing: W warm-up steps, then exactly K timed steps
     K, Wm = args.steps, args.warmup
@@ -163,14 +208,17 @@ def main():
         seconds = time_region(torch, timed, 1)
         launch = f"HIP graph of {ring} layer-steps"
     us_per_step = seconds * 1e6 / K
-    alg_bytes = W.algorithmic_bytes(Hkv, Hq, d, [N] * B, [k] * B)
+    lens_final = [int(n) + (1 if cfg.append else 0) for n in layers[0].lens_host]
+    ks = [int(x) for x in layers[0].k_host]
+    alg_bytes = W.algorithmic_bytes(Hkv, Hq, d, lens_final, ks)
     gbs = alg_bytes / (us_per_step * 1e-6) / 1e9
+    k = k_max
 
     # ---- dominant kernel (GATHER-ATT) by HIP events on its own graph of `ring` launches
     def gather_sweep():
         for s in layers:
             ctx.hashattn_gather_attend(s.q, s.cache, s.idx, s.count, s.B, s.k_max, s.scale, s.out)
-    gather_bytes = W.gathered_bytes(Hq, d, [N] * B, [k] * B)
+    gather_bytes = W.gathered_bytes(Hq, d, lens_final, ks)
     if args.no_graph:
         gather_us = event_time_us(torch, gather_sweep, 10) / ring
     else:
@@ -202,14 +250,14 @@ def main():
             for s in layers:
                 runner.dense_step(ctx, s)
         dense_us = stage_us(dense_sweep)
-        dense_bytes = B * (2 * Hkv * N * d * 2 + 2 * Hq * d * 2)
+        dense_bytes = sum(2 * Hkv * n * d * 2 + 2 * Hq * d * 2 for n in lens_final)
         dense = {"us_per_layer": round(dense_us, 3), "GBps": round(dense_bytes / (dense_us * 1e-6) / 1e9, 1),
                  "speedup_sparse_vs_dense": round(dense_us / us_per_step, 3)}
 
     # ---- CPU oracle on the host cores, same arrays as ring layer 0
     cpu = None
     parity = None
-    if not args.no_cpu_baseline:
+    if host_layer0:
         import oracle
         ok, ov = L0.k.copy(), L0.v.copy()
         codes = np.zeros(ok.shape[:3], dtype=np.uint32)
@@ -243,14 +291,17 @@ def main():
         "ms_per_step": round(us_per_step * 1e-3, 6), "us_per_layer_step": round(us_per_step, 3),
         "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: Llama-3.1-8B-shaped decode layer, B={B}, N={N}, k={k} "
-                               f"({N // k}x sparsity), {Hq} q heads / {Hkv} KV heads, d={d}, "
-                               f"mapping MLPs {'-'.join(map(str, cfg.mlp_dims))} fp32",
-                   "batch": B, "context": N, "k": k, "ring_layers": ring, "launch": launch,
+        "config": {"workload": f"{cfg.name}: Llama-3.1-8B-shaped decode layer, B={B}, N={describe_lengths(lens_final)}, "
+                               f"k={describe_lengths(ks)} ({round(sum(lens_final) / max(sum(ks), 1))}x sparsity), "
+                               f"{Hq} q heads / {Hkv} KV heads, d={d}, mapping MLPs {'-'.join(map(str, cfg.mlp_dims))} fp32"
+                               + (", paged KV (16 tokens/page)" if cfg.page_size else "")
+                               + (", one-token append per step" if cfg.append else ""),
+                   "batch": B, "context": max(lens_final), "k": k, "ring_layers": ring, "launch": launch,
                    "algorithmic_bytes_per_step": alg_bytes},
-        "roofline": {"bound": "hbm", "kernel": "gather_attend_kernel", "achieved": round(gather_gbs, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gather_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": None, "us_per_launch": round(gather_us, 3), "algorithmic_bytes_per_launch": gather_bytes},
+        "roofline": {"bound": "hbm", "kernel": "hashattn_gather_attend = gather_attend_kernel + merge_partials_kernel",
+                     "achieved": round(gather_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gather_gbs / HBM_PEAK_GBS, 4), "traffic": stored_traffic(args.workload),
+                     "us_per_launch": round(gather_us, 3), "algorithmic_bytes_per_launch": gather_bytes},
         "cpu_baseline": cpu,
         "stages_us": {"encode_query": round(encq_us, 3), "score_topk": round(topk_us, 3),
                       "gather_attend": round(gather_us, 3)},
