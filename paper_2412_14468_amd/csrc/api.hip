@@ -121,33 +121,37 @@ ha::KvView view_of(const hashattn_ctx* ctx, const hashattn_kv* kv)
 
 // Tokens per wave unit of SCORE/TOPK: small units fill the chip at short contexts, larger ones
 // keep the number of blocks (and of per-block tables every block has to sum) down at long contexts.
-int pick_unit_tokens(const hashattn_ctx* ctx, int batch, int max_seq_len)
+// `mixed`: the caller gave a k per sequence, so lengths differ; a block is sized by the longest
+// sequence and mostly idle for a short one, hence the smaller cap.
+int pick_unit_tokens(const hashattn_ctx* ctx, int batch, int max_seq_len, bool mixed)
 {
     const int64_t lanes = (int64_t)batch * ctx->cfg.n_kv_heads;
+    const int cap = mixed ? kMaxUnit / 2 : kMaxUnit;
     int unit = kMinUnit;
     auto blocks = [&](int u) { return (max_seq_len + (int64_t)u * ha::kTopkWavesPerBlock - 1) / ((int64_t)u * ha::kTopkWavesPerBlock); };
-    // a 16-wave block fills a CU: prefer one round of blocks over the 256 CUs, never more blocks
-    // per sequence than the scratch pitch
-    while (unit < kMaxUnit && (lanes * blocks(unit) > 256 || blocks(unit) > ctx->blocks_pitch))
-        unit *= 2;
+    // a 16-wave block fills a CU: prefer one round of blocks over the 256 CUs
+    while (unit < cap && lanes * blocks(unit) > 256) unit *= 2;
+    // never more blocks per sequence than the scratch pitch
+    while (unit < kMaxUnit && blocks(unit) > ctx->blocks_pitch) unit *= 2;
     return unit;
 }
 
 // Split shape for the attention kernels: `total` tokens per (sequence, head), `lanes` independent
-// (sequence, head) pairs that share the launch.
-void pick_splits(const hashattn_ctx* ctx, int64_t lanes, int64_t total, int batch, int* chunk, int* n_splits)
+// (sequence, head) pairs that share the launch.  About a thousand blocks fill the chip; pieces of
+// at most `max_chunk` tokens keep a batch of mixed lengths balanced (the grid is sized by the
+// longest list, blocks past the end of a shorter one exit at once).
+void pick_splits(const hashattn_ctx* ctx, int64_t lanes, int64_t total, int batch, int64_t max_chunk, int* chunk, int* n_splits)
 {
     int64_t cap = ctx->part_floats / ((int64_t)batch * ctx->cfg.n_q_heads * ha::kPartStride);
     if (cap > kMaxSplits) cap = kMaxSplits;
     if (cap < 1) cap = 1;
-    int64_t target = 2048, min_chunk = 64;
-    if (const char* e = getenv("HA_BLOCKS_TARGET")) target = atoll(e);
-    if (const char* e = getenv("HA_MIN_CHUNK")) min_chunk = atoll(e);
+    const int64_t target = 1024, min_chunk = 64;
     int64_t want = (target + lanes - 1) / lanes;
     if (want > cap) want = cap;
     if (want < 1) want = 1;
     int64_t c = (total + want - 1) / want;
     c = (c + 63) / 64 * 64;                                    // whole 64-row iterations
+    if (c > max_chunk) c = max_chunk;
     if (c < min_chunk) c = min_chunk;
     int64_t s = (total + c - 1) / c;
     if (s < 1) s = 1;
@@ -203,7 +207,7 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
     const int64_t hist_bytes = bh * pitch * ha::kCumRow * (int64_t)sizeof(int32_t);
     const int64_t unit_bytes = bh * pitch * ha::kTopkWavesPerBlock * ha::kCumRow * (int64_t)sizeof(uint16_t);
     int64_t splits = (cfg->max_context + 63) / 64;               // dense needs more splits than gather
-    int64_t want = 4096 / bh; if (want < 8) want = 8;
+    int64_t want = 8192 / bh; if (want < 16) want = 16;
     if (splits > want) splits = want;
     if (splits > kMaxSplits) splits = kMaxSplits;
     ctx->part_floats = bh * splits * ha::kPartStride;
@@ -289,7 +293,7 @@ hashattn_status hashattn_score_topk(hashattn_ctx* ctx, const uint32_t* q_codes, 
     if (k_max < 1) return fail(ctx, HASHATTN_INVALID_ARG, "score_topk: k_max %d < 1", k_max);
     if (k_max > ctx->cfg.max_k) return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "score_topk: k_max %d exceeds max_k %lld", k_max, (long long)ctx->cfg.max_k);
     const ha::TopkScratch sc{ctx->blk_cum, ctx->unit_cum, ctx->blocks_pitch};
-    const int unit = pick_unit_tokens(ctx, batch, cache->max_seq_len);
+    const int unit = pick_unit_tokens(ctx, batch, cache->max_seq_len, k_per_seq != nullptr);
     const hipError_t e = ha::launch_score_topk(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group, q_codes, batch,
                                                ctx->cfg.n_q_heads, k_per_seq, k_max, cache->max_seq_len, unit, sc,
                                                idx, count, threshold, static_cast<hipStream_t>(stream));
@@ -309,7 +313,7 @@ hashattn_status hashattn_gather_attend(hashattn_ctx* ctx, const void* q, const h
     if (k_max > ctx->cfg.max_k) return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "gather_attend: k_max %d exceeds max_k %lld", k_max, (long long)ctx->cfg.max_k);
     if (!(scale == scale)) return fail(ctx, HASHATTN_INVALID_ARG, "gather_attend: scale is NaN");
     int chunk, n_splits;
-    pick_splits(ctx, (int64_t)batch * ctx->cfg.n_q_heads, k_max, batch, &chunk, &n_splits);
+    pick_splits(ctx, (int64_t)batch * ctx->cfg.n_q_heads, k_max, batch, 512, &chunk, &n_splits);
     const hipError_t e = ha::launch_gather_attend(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group,
                                                   static_cast<const uint16_t*>(q), idx, count, batch, ctx->cfg.n_q_heads,
                                                   k_max, chunk, n_splits, scale, ctx->part, static_cast<uint16_t*>(out),
@@ -327,7 +331,7 @@ hashattn_status hashattn_dense_attend(hashattn_ctx* ctx, const void* q, const ha
     if (!(scale == scale)) return fail(ctx, HASHATTN_INVALID_ARG, "dense_attend: scale is NaN");
     int chunk, n_splits;
     const int64_t total = cache->max_seq_len > 0 ? cache->max_seq_len : 1;
-    pick_splits(ctx, (int64_t)batch * ctx->cfg.n_kv_heads, total, batch, &chunk, &n_splits);
+    pick_splits(ctx, (int64_t)batch * ctx->cfg.n_kv_heads, total, batch, 16384, &chunk, &n_splits);
     const hipError_t e = ha::launch_dense_attend(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group,
                                                  static_cast<const uint16_t*>(q), batch, ctx->cfg.n_q_heads,
                                                  cache->max_seq_len, chunk, n_splits, scale, ctx->part,

@@ -183,16 +183,28 @@ __global__ __launch_bounds__(WAVES * 64) void gather_attend_kernel(KvView c, con
     __shared__ float red;
     const int tid = threadIdx.x, lane = tid & 63, sub = lane & 15;
     const int slot = tid >> 4;                       // 0..kSlots-1
-    const int split = blockIdx.x, hq = blockIdx.y, b = blockIdx.z, kvh = hq / group;
+    const int hq = blockIdx.y, b = blockIdx.z, kvh = hq / group;
+    const int split = rotated_block(blockIdx.x, hq + b, n_splits);
     const int64_t bh = (int64_t)b * n_q_heads + hq;
     const int32_t* my_idx = idx + bh * k_max;
     const int begin = split * chunk;
 
-    // the first index loads do not wait for the count: slots past it are valid memory, their
-    // contents are only used once known to be below the count
-    int tok[4];
+    // Three loads chain up for a row: its list entry, (paged) the page-table entry of that token,
+    // the row itself.  They run as a pipeline over the iterations: while rows i are consumed, rows
+    // i+1 are in flight, page entries i+2 have been asked for and list entries i+3 are requested,
+    // so no iteration waits on a load it has issued itself.  Loads complete in issue order, which
+    // is why every iteration issues the small loads before the rows.
+    // The first list loads do not wait for the count: entries past it are valid memory, their
+    // contents are only used once known to be below the count.
+    auto list_at = [&](int r) { return my_idx[min(r, k_max - 1)]; };
+    int tok0[4], tok1[4], tok2[4];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) tok[i] = my_idx[min(begin + i * kSlots + slot, k_max - 1)];
+    for (int i = 0; i < 4; ++i) {
+        const int r = begin + i * kSlots + slot;
+        tok0[i] = list_at(r);
+        tok1[i] = list_at(r + kRowsPerIter);
+        tok2[i] = list_at(r + 2 * kRowsPerIter);
+    }
     const int cnt = min(count[bh], k_max);
     const uint4 qraw = *reinterpret_cast<const uint4*>(q + bh * kHeadDim + sub * 8);
     if (begin >= cnt) {
@@ -212,31 +224,40 @@ __global__ __launch_bounds__(WAVES * 64) void gather_attend_kernel(KvView c, con
 
     const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
     uint4 kr[4], vr[4];
-    bool ok[4];
+    bool ok[4], ok1[4];
+    int pg1[4];                                      // page entries of the rows one iteration ahead
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        ok[i] = begin + i * kSlots + slot < end;
+        const int r = begin + i * kSlots + slot;
+        ok[i] = r < end;
+        ok1[i] = r + kRowsPerIter < end;
+        const int pg0 = ok[i] ? page_of<PAGED>(c, b, tok0[i]) : 0;
+        pg1[i] = ok1[i] ? page_of<PAGED>(c, b, tok1[i]) : 0;
         kr[i] = zero4;
         vr[i] = zero4;
         if (ok[i]) {
-            const int64_t row = row_of<PAGED>(c, b, kvh, tok[i]);
+            const int64_t row = row_in_page<PAGED>(c, b, kvh, tok0[i], pg0);
             kr[i] = load_row16(c.k, row, sub);
             vr[i] = load_row16(c.v, row, sub);
         }
     }
     for (int base = begin; base < end; base += kRowsPerIter) {
-        // issue the next 64 rows before consuming the current ones
-        const int nbase = base + kRowsPerIter;
+        int pg2[4], tok3[4];
+        bool ok2[4];
         uint4 kn[4], vn[4];
-        bool okn[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int r = nbase + i * kSlots + slot;
-            okn[i] = r < end;
+            const int r = base + i * kSlots + slot;
+            ok2[i] = r + 2 * kRowsPerIter < end;
+            pg2[i] = ok2[i] ? page_of<PAGED>(c, b, tok2[i]) : 0;
+            tok3[i] = r + 3 * kRowsPerIter < end ? my_idx[r + 3 * kRowsPerIter] : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
             kn[i] = zero4;
             vn[i] = zero4;
-            if (okn[i]) {
-                const int64_t row = row_of<PAGED>(c, b, kvh, my_idx[r]);
+            if (ok1[i]) {
+                const int64_t row = row_in_page<PAGED>(c, b, kvh, tok1[i], pg1[i]);
                 kn[i] = load_row16(c.k, row, sub);
                 vn[i] = load_row16(c.v, row, sub);
             }
@@ -249,7 +270,12 @@ __global__ __launch_bounds__(WAVES * 64) void gather_attend_kernel(KvView c, con
         }
         absorb4(x, vr, m, l, acc);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { kr[i] = kn[i]; vr[i] = vn[i]; ok[i] = okn[i]; }
+        for (int i = 0; i < 4; ++i) {
+            kr[i] = kn[i]; vr[i] = vn[i];
+            ok[i] = ok1[i]; ok1[i] = ok2[i];
+            tok1[i] = tok2[i]; tok2[i] = tok3[i];
+            pg1[i] = pg2[i];
+        }
     }
 
     // a group that saw no valid row keeps m = -inf, l = 0 (possible when end - begin < 16)
@@ -273,7 +299,8 @@ __global__ __launch_bounds__(256) void dense_attend_kernel(KvView c, const uint1
     __shared__ float st[kSlots * kPartStride];
     const int tid = threadIdx.x, lane = tid & 63, sub = lane & 15;
     const int slot = tid >> 4;
-    const int split = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+    const int kvh = blockIdx.y, b = blockIdx.z;
+    const int split = rotated_block(blockIdx.x, kvh + b, n_splits);
     const int n = min(c.seq_lens[b], n_cap);
     const int begin = split * chunk;
     const int64_t bh0 = (int64_t)b * n_q_heads + kvh * G;
@@ -290,33 +317,43 @@ __global__ __launch_bounds__(256) void dense_attend_kernel(KvView c, const uint1
         for (int e = 0; e < 8; ++e) { qf[j][e] *= scale_log2e; acc[j][e] = 0.f; }
     }
 
+    // rows one iteration ahead, their page-table entries two ahead (see gather_attend_kernel)
     const uint4 zero4 = make_uint4(0u, 0u, 0u, 0u);
     uint4 kr[4], vr[4];
-    bool ok[4];
+    bool ok[4], ok1[4];
+    int pg1[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int t = begin + i * kSlots + slot;
         ok[i] = t < end;
+        ok1[i] = t + kRowsPerIter < end;
+        const int pg0 = ok[i] ? page_of<PAGED>(c, b, t) : 0;
+        pg1[i] = ok1[i] ? page_of<PAGED>(c, b, t + kRowsPerIter) : 0;
         kr[i] = zero4;
         vr[i] = zero4;
         if (ok[i]) {
-            const int64_t row = row_of<PAGED>(c, b, kvh, t);
+            const int64_t row = row_in_page<PAGED>(c, b, kvh, t, pg0);
             kr[i] = load_row16(c.k, row, sub);
             vr[i] = load_row16(c.v, row, sub);
         }
     }
     for (int base = begin; base < end; base += kRowsPerIter) {
-        const int nbase = base + kRowsPerIter;
         uint4 kn[4], vn[4];
-        bool okn[4];
+        bool ok2[4];
+        int pg2[4];
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const int t = nbase + i * kSlots + slot;
-            okn[i] = t < end;
+            const int t = base + 2 * kRowsPerIter + i * kSlots + slot;
+            ok2[i] = t < end;
+            pg2[i] = ok2[i] ? page_of<PAGED>(c, b, t) : 0;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int t = base + kRowsPerIter + i * kSlots + slot;
             kn[i] = zero4;
             vn[i] = zero4;
-            if (okn[i]) {
-                const int64_t row = row_of<PAGED>(c, b, kvh, t);
+            if (ok1[i]) {
+                const int64_t row = row_in_page<PAGED>(c, b, kvh, t, pg1[i]);
                 kn[i] = load_row16(c.k, row, sub);
                 vn[i] = load_row16(c.v, row, sub);
             }
@@ -332,7 +369,11 @@ __global__ __launch_bounds__(256) void dense_attend_kernel(KvView c, const uint1
             absorb4(x, vr, m[j], l[j], acc[j]);
         }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) { kr[i] = kn[i]; vr[i] = vn[i]; ok[i] = okn[i]; }
+        for (int i = 0; i < 4; ++i) {
+            kr[i] = kn[i]; vr[i] = vn[i];
+            ok[i] = ok1[i]; ok1[i] = ok2[i];
+            pg1[i] = pg2[i];
+        }
     }
 
     float* mine = st + slot * kPartStride;

@@ -39,6 +39,22 @@ __device__ __forceinline__ int64_t row_of(const KvView& c, int b, int h, int t)
     }
 }
 
+// The same in two steps, for callers that fetch the page-table entry ahead of time
+// (0 when the cache is contiguous).
+template <bool PAGED>
+__device__ __forceinline__ int page_of(const KvView& c, int b, int t)
+{
+    if constexpr (PAGED) return c.page_table[(int64_t)b * c.max_pages_per_seq + (t >> 4)];
+    else return 0;
+}
+
+template <bool PAGED>
+__device__ __forceinline__ int64_t row_in_page(const KvView& c, int b, int h, int t, int page)
+{
+    if constexpr (PAGED) return ((int64_t)page * c.n_kv_heads + h) * kPage + (t & (kPage - 1));
+    else return ((int64_t)b * c.n_kv_heads + h) * c.n_max + t;
+}
+
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
 
@@ -113,5 +129,14 @@ __device__ __forceinline__ int lanes_below(uint64_t mask)
 }
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
+
+// Workgroups go to the eight XCDs round-robin in launch order, x fastest.  With the piece index
+// of a (sequence, head) in blockIdx.x and a piece count that divides (or is divided by) eight,
+// piece p of every list would land on the same XCD, and in a batch of mixed lengths the high
+// pieces exist for long sequences only.  Rotating by the list's index spreads them.
+__device__ __forceinline__ int rotated_block(unsigned x, int list, int n)
+{
+    return (int)((x + (unsigned)list) % (unsigned)n);
+}
 
 }  // namespace ha

@@ -59,9 +59,10 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
     __shared__ int bsum[G * kBins];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int b = blockIdx.z, kvh = blockIdx.y;
-    const int unit = blockIdx.x * kWpb + wave;
+    const int bx = rotated_block(blockIdx.x, kvh + b, gridDim.x);      // block index inside the sequence
+    const int unit = bx * kWpb + wave;
     const int n = min(c.seq_lens[b], n_cap);   // n_cap: the host's bound that sized grid and scratch
-    if ((int64_t)blockIdx.x * kWpb * unit_tokens >= n) return;      // whole block beyond the sequence
+    if ((int64_t)bx * kWpb * unit_tokens >= n) return;      // whole block beyond the sequence
     const int64_t t_begin = (int64_t)unit * unit_tokens;
     const bool active = t_begin < n;
     const int t_end = (int)min((int64_t)n, t_begin + unit_tokens);
@@ -125,7 +126,7 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
         const int total = __builtin_amdgcn_readlane(incl, 63);
         if (lane < kCumRow) {
             const int64_t bh = (int64_t)b * n_q_heads + kvh * G + j;
-            blk_cum[(bh * blocks_pitch + blockIdx.x) * kCumRow + lane] = total - incl + h;
+            blk_cum[(bh * blocks_pitch + bx) * kCumRow + lane] = total - incl + h;
         }
     }
 }
@@ -257,7 +258,8 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
     __shared__ int thr[G];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int b = blockIdx.z, kvh = blockIdx.y;
-    const int unit0 = blockIdx.x * kWpb, unit = unit0 + wave;
+    const int bx = rotated_block(blockIdx.x, kvh + b, gridDim.x);      // block index inside the sequence
+    const int unit0 = bx * kWpb, unit = unit0 + wave;
     const int64_t bh0 = (int64_t)b * n_q_heads + kvh * G;
     const int nb_cap = gridDim.x;                              // blocks the host launched per sequence
 
@@ -283,7 +285,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
     const int n = min(n_raw, n_cap);
     const int k = max(0, min(k_raw, min(k_max, n)));
     const int block_tokens = kWpb * unit_tokens;
-    if (blockIdx.x > 0 && ((int64_t)blockIdx.x * block_tokens >= n || k == 0)) return;   // block 0 reports the counts
+    if (bx > 0 && ((int64_t)bx * block_tokens >= n || k == 0)) return;   // block 0 reports the counts
     const int n_blocks = (n + block_tokens - 1) / block_tokens;
     const int n_units = (n + unit_tokens - 1) / unit_tokens;
     const int64_t t_begin = (int64_t)unit * unit_tokens;
@@ -320,7 +322,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
             const uint64_t ge_k = __ballot(lane < kBins && cum >= k);   // lane 0 is set: cum(0) = n >= k
             T = 63 - __clzll((long long)(ge_k | 1ull));
             r = k - __shfl(cum, T + 1, kWave);                          // slot 33 holds 0
-            for (int blk = lane; blk < (int)blockIdx.x; blk += kWave) {
+            for (int blk = lane; blk < bx; blk += kWave) {
                 ge += tab[blk * kCumRow + T];
                 gt += tab[blk * kCumRow + T + 1];
             }
@@ -340,7 +342,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
         }
         if (lane == 0) {
             thr[j] = T;
-            if (blockIdx.x == 0) {
+            if (bx == 0) {
                 count[bh] = k;
                 if (threshold) threshold[bh] = (uint8_t)(k > 0 ? T : 0);
             }
