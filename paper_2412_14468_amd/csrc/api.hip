@@ -15,7 +15,6 @@ struct hashattn_ctx {
     int group;
     // TOPK scratch
     int32_t* blk_cum;
-    uint16_t* unit_cum;
     int32_t blocks_pitch;
     // split partials shared by GATHER-ATT and the dense kernel
     float* part;
@@ -205,21 +204,23 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
     if (pitch > ha::kMaxTopkBlocks) pitch = ha::kMaxTopkBlocks;
     ctx->blocks_pitch = (int32_t)pitch;
     const int64_t hist_bytes = bh * pitch * ha::kCumRow * (int64_t)sizeof(int32_t);
-    const int64_t unit_bytes = bh * pitch * ha::kTopkWavesPerBlock * ha::kCumRow * (int64_t)sizeof(uint16_t);
     int64_t splits = (cfg->max_context + 63) / 64;               // dense needs more splits than gather
     int64_t want = 8192 / bh; if (want < 16) want = 16;
     if (splits > want) splits = want;
     if (splits > kMaxSplits) splits = kMaxSplits;
     ctx->part_floats = bh * splits * ha::kPartStride;
     const int64_t part_bytes = ctx->part_floats * (int64_t)sizeof(float);
-    ctx->scratch_bytes = hist_bytes + unit_bytes + part_bytes;
+    ctx->scratch_bytes = hist_bytes + part_bytes;
 
     if ((e = hipMalloc(reinterpret_cast<void**>(&ctx->blk_cum), hist_bytes)) != hipSuccess ||
-        (e = hipMalloc(reinterpret_cast<void**>(&ctx->unit_cum), unit_bytes)) != hipSuccess ||
         (e = hipMalloc(reinterpret_cast<void**>(&ctx->part), part_bytes)) != hipSuccess) {
         const long long wanted = (long long)ctx->scratch_bytes;
         hashattn_destroy(ctx);
         return fail(nullptr, HASHATTN_HIP_ERROR, "create: allocating %lld scratch bytes: %s", wanted, hipGetErrorString(e));
+    }
+    if ((e = ha::setup_score_topk(group)) != hipSuccess) {
+        hashattn_destroy(ctx);
+        return fail(nullptr, HASHATTN_HIP_ERROR, "create: raising the LDS limit of the TOPK kernels: %s", hipGetErrorString(e));
     }
     *out = ctx;
     return HASHATTN_OK;
@@ -229,7 +230,6 @@ hashattn_status hashattn_destroy(hashattn_ctx* ctx)
 {
     if (!ctx) return HASHATTN_OK;
     if (ctx->blk_cum) (void)hipFree(ctx->blk_cum);
-    if (ctx->unit_cum) (void)hipFree(ctx->unit_cum);
     if (ctx->part) (void)hipFree(ctx->part);
     delete ctx;
     return HASHATTN_OK;
@@ -292,7 +292,7 @@ hashattn_status hashattn_score_topk(hashattn_ctx* ctx, const uint32_t* q_codes, 
         return fail(ctx, HASHATTN_INVALID_ARG, "score_topk: 4-byte alignment required");
     if (k_max < 1) return fail(ctx, HASHATTN_INVALID_ARG, "score_topk: k_max %d < 1", k_max);
     if (k_max > ctx->cfg.max_k) return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "score_topk: k_max %d exceeds max_k %lld", k_max, (long long)ctx->cfg.max_k);
-    const ha::TopkScratch sc{ctx->blk_cum, ctx->unit_cum, ctx->blocks_pitch};
+    const ha::TopkScratch sc{ctx->blk_cum, ctx->blocks_pitch};
     const int unit = pick_unit_tokens(ctx, batch, cache->max_seq_len, k_per_seq != nullptr);
     const hipError_t e = ha::launch_score_topk(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group, q_codes, batch,
                                                ctx->cfg.n_q_heads, k_per_seq, k_max, cache->max_seq_len, unit, sc,
@@ -331,7 +331,8 @@ hashattn_status hashattn_dense_attend(hashattn_ctx* ctx, const void* q, const ha
     if (!(scale == scale)) return fail(ctx, HASHATTN_INVALID_ARG, "dense_attend: scale is NaN");
     int chunk, n_splits;
     const int64_t total = cache->max_seq_len > 0 ? cache->max_seq_len : 1;
-    pick_splits(ctx, (int64_t)batch * ctx->cfg.n_kv_heads, total, batch, 16384, &chunk, &n_splits);
+    const int64_t lanes = (int64_t)batch * ctx->cfg.n_kv_heads;
+    pick_splits(ctx, lanes, total, batch, lanes > 128 ? 4096 : 16384, &chunk, &n_splits);   // measured on C2 / C4 shapes
     const hipError_t e = ha::launch_dense_attend(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group,
                                                  static_cast<const uint16_t*>(q), batch, ctx->cfg.n_q_heads,
                                                  cache->max_seq_len, chunk, n_splits, scale, ctx->part,

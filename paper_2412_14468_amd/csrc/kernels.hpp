@@ -15,7 +15,6 @@ struct MlpView {
 
 struct TopkScratch {
     int32_t* blk_cum;      // [B][Hq][blocks_pitch][34]: per block of 16 units, #{score >= s}
-    uint16_t* unit_cum;    // [B][Hq][blocks_pitch * 16][34]: the same per unit
     int32_t blocks_pitch;
 };
 
@@ -25,6 +24,8 @@ hipError_t launch_encode_query(const MlpView& phi, const uint16_t* q, int batch,
 hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
                               const uint16_t* k_new, const uint16_t* v_new,
                               int batch, int64_t n_new, int max_seq_len, hipStream_t stream);
+
+hipError_t setup_score_topk(int group);
 
 hipError_t launch_score_topk(const KvView& kv, bool paged, int group, const uint32_t* q_codes,
                              int batch, int n_q_heads, const int32_t* k_per_seq, int k_max,

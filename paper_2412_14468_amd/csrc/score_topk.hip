@@ -6,18 +6,25 @@
 // of 16 waves owns 16 consecutive units of one KV head and serves the G query heads
 // of its group from one read of the codes.
 //   1. score_hist   every wave scores its unit for the G heads and counts scores per
-//                   head in LDS; the cumulative counts C(s) = #{score >= s} are stored
-//                   per unit and per block (one coalesced row per head each).
-//   2. topk_select  every block sums the per-block rows of its heads to get the
-//                   threshold T (largest T with #{score >= T} >= k) and the tie quota
-//                   r = k - #{score > T}; rows T and T + 1 of the blocks before it and of
-//                   its own units give every wave its first output slot and its share of
-//                   the quota (block and unit order = token order, so ties go to the lower
-//                   token index).  Each wave then re-scores its unit into per-lane bit
-//                   masks and writes the selected token ids at offset + rank, ranks
-//                   coming from packed wave prefix sums in token order.  The result is
-//                   ascending by index and does not depend on the order in which waves
-//                   or blocks run.
+//                   head in one LDS histogram per block.  A bin has 32 copies, picked
+//                   by lane, so the 64 adds of a wave instruction fall on 32 different
+//                   banks whatever the scores are (with the copies of a bin side by
+//                   side the adds of a wave cost about 2 LDS passes; with a histogram
+//                   per wave and 4 copies per bin they cost about 10).  The cumulative
+//                   counts C(s) = #{score >= s} of the block go to one row per head.
+//   2. topk_select  every block sums the rows of its heads to get the threshold T
+//                   (largest T with C(T) >= k) and the tie quota r = k - C(T + 1); rows
+//                   T and T + 1 of the blocks before it give its first output slot and
+//                   its share of the quota (block order = token order, so ties go to the
+//                   lower token index).  Each wave re-scores its unit into one bit mask
+//                   per lane and head, the waves of the block exchange their counts
+//                   through LDS, and each wave writes the selected token ids at
+//                   offset + rank.  For that the codes are first moved through LDS so
+//                   that a lane holds consecutive tokens: the rank of a token is then
+//                   the lane's prefix count plus the bits below it, one wave prefix sum
+//                   serves two heads, and the ids of a lane leave in a loop over its set
+//                   bits.  The result is ascending by index and does not depend on the
+//                   order in which waves or blocks run.
 // Scores never go to HBM; the codes are read twice (the second read mostly from
 // L2 / Infinity Cache).  All loads of a unit are issued before the first is used.
 // Nothing persists between calls.
@@ -28,34 +35,52 @@ namespace ha {
 namespace {
 
 constexpr int kAllTies = 0x7fffffff;
-constexpr int kCopies = 4;            // LDS histogram copies per wave (by lane & 3): fewer same-address adds
-constexpr int kChunk = 4 * 4 * kWave; // tokens a wave loads at once: four 16-byte loads per lane
+constexpr int kBinCopies = 32;        // LDS copies of a histogram bin, one per bank
+constexpr int kChunk = 4 * 4 * kWave; // most tokens a wave handles at once: four 16-byte loads per lane
 constexpr int kWpb = kTopkWavesPerBlock;
 constexpr int kThreads = kWpb * kWave;
 
-template <bool PAGED>
+// NIT 16-byte loads per lane, coalesced: load `it` of lane L holds tokens base + it * 256 + 4 L .. + 3.
+template <bool PAGED, int NIT>
 __device__ __forceinline__ void load_chunk(const KvView& c, int b, int kvh, int base, int t_end, int lane,
-                                           uint4 (&cw)[4])
+                                           uint4 (&cw)[NIT])
 {
 #pragma unroll
-    for (int it = 0; it < 4; ++it) {
+    for (int it = 0; it < NIT; ++it) {
         const int t0 = base + it * 4 * kWave + lane * 4;
         cw[it] = make_uint4(0u, 0u, 0u, 0u);
         if (t0 < t_end) cw[it] = *reinterpret_cast<const uint4*>(c.codes + row_of<PAGED>(c, b, kvh, t0));
     }
 }
 
-// Tables written by score_hist and read by topk_select; a row holds #{score >= s} for s = 0..32 and
+template <int G, bool CHECKED>
+__device__ __forceinline__ void count_chunk(const uint4 (&cw)[4], int base, int t_end, int lane,
+                                            const uint32_t (&qc)[G], unsigned* mine)
+{
+#pragma unroll
+    for (int it = 0; it < 4; ++it) {
+        const int t0 = base + it * 4 * kWave + lane * 4;
+        const uint32_t w[4] = {cw[it].x, cw[it].y, cw[it].z, cw[it].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            if (!CHECKED || t0 + e < t_end) {
+#pragma unroll
+                for (int j = 0; j < G; ++j)       // score = popcount of the agreeing bits
+                    atomicAdd(&mine[(j * kBins + __popc(~(w[e] ^ qc[j]))) * kBinCopies], 1u);
+            }
+        }
+    }
+}
+
+// Table written by score_hist and read by topk_select; a row holds #{score >= s} for s = 0..32 and
 // a zero in slot 33, so that "row[T + 1]" is valid for T = 32:
 //   blk_cum:  [B][Hq][blocks_pitch][34] ints, one row per block of 16 units
-//   unit_cum: [B][Hq][blocks_pitch * 16][34] uint16, one row per unit
 template <int G, bool PAGED>
 __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const uint32_t* __restrict__ q_codes,
                                                               int n_q_heads, int n_cap, int unit_tokens,
-                                                              int blocks_pitch, int32_t* __restrict__ blk_cum,
-                                                              uint16_t* __restrict__ unit_cum)
+                                                              int blocks_pitch, int32_t* __restrict__ blk_cum)
 {
-    __shared__ unsigned hist[kWpb][kCopies][G * kBins];
+    __shared__ __attribute__((aligned(16))) unsigned hist[G * kBins * kBinCopies];   // [head][score][copy]
     __shared__ int bsum[G * kBins];
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int b = blockIdx.z, kvh = blockIdx.y;
@@ -68,33 +93,21 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
     const int t_end = (int)min((int64_t)n, t_begin + unit_tokens);
 
     uint4 cw[4];
-    if (active) load_chunk<PAGED>(c, b, kvh, (int)t_begin, t_end, lane, cw);
+    if (active) load_chunk<PAGED, 4>(c, b, kvh, (int)t_begin, t_end, lane, cw);
     uint32_t qc[G];
 #pragma unroll
     for (int j = 0; j < G; ++j) qc[j] = (uint32_t)uniform((int)q_codes[(int64_t)b * n_q_heads + kvh * G + j]);
-    for (int i = lane; i < kCopies * G * kBins; i += kWave) (&hist[wave][0][0])[i] = 0u;
-    for (int i = tid; i < G * kBins; i += kThreads) bsum[i] = 0;
+    for (int i = tid; i < G * kBins * kBinCopies; i += kThreads) hist[i] = 0u;
     __syncthreads();
 
     if (active) {
-        unsigned* mine = hist[wave][lane & (kCopies - 1)];
+        unsigned* mine = hist + (lane & (kBinCopies - 1));
         for (int base = (int)t_begin; base < t_end; base += kChunk) {
             uint4 nx[4];
             const bool more = base + kChunk < t_end;
-            if (more) load_chunk<PAGED>(c, b, kvh, base + kChunk, t_end, lane, nx);
-#pragma unroll
-            for (int it = 0; it < 4; ++it) {
-                const int t0 = base + it * 4 * kWave + lane * 4;
-                const uint32_t w[4] = {cw[it].x, cw[it].y, cw[it].z, cw[it].w};
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if (t0 + e < t_end) {
-#pragma unroll
-                        for (int j = 0; j < G; ++j)
-                            atomicAdd(&mine[j * kBins + kBits - __popc(w[e] ^ qc[j])], 1u);
-                    }
-                }
-            }
+            if (more) load_chunk<PAGED, 4>(c, b, kvh, base + kChunk, t_end, lane, nx);
+            if (base + kChunk <= t_end) count_chunk<G, false>(cw, base, t_end, lane, qc, mine);
+            else count_chunk<G, true>(cw, base, t_end, lane, qc, mine);     // ragged end of the sequence
             if (more) {
 #pragma unroll
                 for (int it = 0; it < 4; ++it) cw[it] = nx[it];
@@ -102,24 +115,17 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
         }
     }
     __syncthreads();
-    // per unit: cumulative counts per head by a wave scan (lanes 0..32 hold the bins, lane 33 the zero slot)
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
-        int h = 0;
-        if (lane < kBins) {
-#pragma unroll
-            for (int cp = 0; cp < kCopies; ++cp) h += (int)hist[wave][cp][j * kBins + lane];
-            if (h) atomicAdd(&bsum[j * kBins + lane], h);
-        }
-        const int incl = wave_incl_scan_i32(h);
-        const int total = __builtin_amdgcn_readlane(incl, 63);
-        if (active && lane < kCumRow) {
-            const int64_t bh = (int64_t)b * n_q_heads + kvh * G + j;
-            unit_cum[(bh * blocks_pitch * kWpb + unit) * kCumRow + lane] = (uint16_t)(total - incl + h);
-        }
+    // the 32 copies of a bin: four threads add eight each, then across the quad
+    for (int row = tid >> 2; row < G * kBins; row += kThreads / 4) {
+        const uint4* p = reinterpret_cast<const uint4*>(hist + row * kBinCopies + (tid & 3) * 8);
+        const uint4 a = p[0], d = p[1];
+        int s = (int)((a.x + a.y) + (a.z + a.w) + (d.x + d.y) + (d.z + d.w));
+        s += dpp_i<0xB1>(s);    // quad_perm:[1,0,3,2]
+        s += dpp_i<0x4E>(s);    // quad_perm:[2,3,0,1]
+        if ((tid & 3) == 0) bsum[row] = s;
     }
     __syncthreads();
-    // per block: the same from the block's summed counts
+    // cumulative counts per head by a wave scan (lanes 0..32 hold the bins, lane 33 the zero slot)
     for (int j = wave; j < G; j += kWpb) {
         const int h = lane < kBins ? bsum[j * kBins + lane] : 0;
         const int incl = wave_incl_scan_i32(h);
@@ -131,135 +137,106 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
     }
 }
 
-// Mask of one lane's tokens of a chunk (bit it * 4 + e, it < NIT) whose Hamming distance to qc is <= lim.
-template <int NIT>
-__device__ __forceinline__ unsigned near_mask(const uint4 (&cw)[4], uint32_t qc, int lim)
+// Bit p of the result: token p of the lane has Hamming distance <= lim (or == dist) to qc.
+template <int TPL>
+__device__ __forceinline__ unsigned within_mask(const uint32_t (&w)[TPL], uint32_t qc, int lim)
 {
     unsigned m = 0;
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const uint32_t w[4] = {cw[it].x, cw[it].y, cw[it].z, cw[it].w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) m |= (unsigned)((int)__popc(w[e] ^ qc) <= lim) << (it * 4 + e);
-    }
+    for (int p = TPL - 1; p >= 0; --p) m = (m << 1) | (unsigned)((int)__popc(w[p] ^ qc) <= lim);
     return m;
 }
 
-template <int NIT>
-__device__ __forceinline__ unsigned equal_mask(const uint4 (&cw)[4], uint32_t qc, int dist)
+template <int TPL>
+__device__ __forceinline__ unsigned equal_mask(const uint32_t (&w)[TPL], uint32_t qc, int dist)
 {
     unsigned m = 0;
 #pragma unroll
-    for (int it = 0; it < NIT; ++it) {
-        const uint32_t w[4] = {cw[it].x, cw[it].y, cw[it].z, cw[it].w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) m |= (unsigned)((int)__popc(w[e] ^ qc) == dist) << (it * 4 + e);
-    }
+    for (int p = TPL - 1; p >= 0; --p) m = (m << 1) | (unsigned)((int)__popc(w[p] ^ qc) == dist);
     return m;
 }
 
-// Lane-exclusive prefix counts of the 4-bit groups of m (NIT of them) over the wave, and the wave totals.
-// Two 16-bit fields per register, so one scan serves two groups (a group holds at most 256).
-template <int NIT>
-__device__ __forceinline__ void group_ranks(unsigned m, int (&excl)[4], int (&total)[4])
+__device__ __forceinline__ void wave_lds_order()
 {
-    const int c0 = __popc(m & 0xfu), c1 = __popc(m & 0xf0u);
-    const int i01 = wave_incl_scan_i32(c0 | (c1 << 16));
-    const int t01 = __builtin_amdgcn_readlane(i01, 63);
-    excl[0] = (i01 & 0xffff) - c0;
-    excl[1] = (int)((unsigned)i01 >> 16) - c1;
-    total[0] = t01 & 0xffff;
-    total[1] = (int)((unsigned)t01 >> 16);
-    excl[2] = excl[3] = total[2] = total[3] = 0;
-    if constexpr (NIT > 2) {
-        const int c2 = __popc(m & 0xf00u), c3 = __popc(m & 0xf000u);
-        const int i23 = wave_incl_scan_i32(c2 | (c3 << 16));
-        const int t23 = __builtin_amdgcn_readlane(i23, 63);
-        excl[2] = (i23 & 0xffff) - c2;
-        excl[3] = (int)((unsigned)i23 >> 16) - c3;
-        total[2] = t23 & 0xffff;
-        total[3] = (int)((unsigned)t23 >> 16);
-    }
+    // LDS accesses of one wave execute in program order; this only keeps the compiler from
+    // moving them across the point where lanes read what other lanes of the wave wrote
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
-// Compaction of one chunk (NIT groups of 256 tokens starting at `base`) of one wave for its G heads.
-template <int G, int NIT>
-__device__ __forceinline__ void compact_chunk(const uint4 (&cw)[4], int base, int t_end, int lane,
-                                              const uint32_t (&qc)[G], const int (&lim)[G], const int (&quota)[G],
-                                              int (&pos)[G], int (&ties_seen)[G], int32_t* __restrict__ idx0,
-                                              int k_max)
+// From the coalesced load layout to runs: afterwards lane L holds tokens base + L * TPL .. + TPL - 1
+// (TPL = 4 NIT) in w.  `stage` is the wave's own LDS area of 64 * (NIT + 1) 16-byte slots; the odd
+// pitch keeps the 16-byte reads of neighbouring lanes on different banks.
+template <int NIT>
+__device__ __forceinline__ void to_lane_runs(const uint4 (&cw)[NIT], uint4* stage, int lane, uint32_t (&w)[NIT * 4])
 {
-    unsigned valid = 0xffffu;                             // tokens of this lane that exist
-    if (base + NIT * 4 * kWave > t_end) {                 // ragged last chunk (uniform over the wave)
-        valid = 0;
-#pragma unroll
-        for (int it = 0; it < NIT; ++it)
-#pragma unroll
-            for (int e = 0; e < 4; ++e)
-                valid |= (unsigned)(base + it * 4 * kWave + lane * 4 + e < t_end) << (it * 4 + e);
-    }
-#pragma unroll
-    for (int j = 0; j < G; ++j) {
-        unsigned m = near_mask<NIT>(cw, qc[j], lim[j]) & valid;
-        if (quota[j] != kAllTies && quota[j] != 0) {
-            // the unit where the tie quota runs out: ties are ranked in token order
-            const unsigned ties = equal_mask<NIT>(cw, qc[j], lim[j] + 1) & valid;
-            int ex[4], tt[4];
-            group_ranks<NIT>(ties, ex, tt);
-            int before_group = ties_seen[j];
-#pragma unroll
-            for (int it = 0; it < NIT; ++it) {
-                int rank = before_group + ex[it];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const unsigned bit = 1u << (it * 4 + e);
-                    if (ties & bit) {
-                        if (rank < quota[j]) m |= bit;
-                        ++rank;
-                    }
-                }
-                before_group += tt[it];
-            }
-            ties_seen[j] = before_group;
-        }
-        int ex[4], tt[4];
-        group_ranks<NIT>(m, ex, tt);
-        int32_t* out = idx0 + (int64_t)j * k_max;
-        int group_start = pos[j];
+    if constexpr (NIT == 1) {
+        w[0] = cw[0].x; w[1] = cw[0].y; w[2] = cw[0].z; w[3] = cw[0].w;
+    } else {
+        constexpr int kPitch = NIT + 1;
+        wave_lds_order();                            // earlier reads of the area are done
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
-            int rank = group_start + ex[it];
-            const int t0 = base + it * 4 * kWave + lane * 4;
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                if (m & (1u << (it * 4 + e))) {
-                    if (rank < k_max) out[rank] = t0 + e;
-                    ++rank;
-                }
-            }
-            group_start += tt[it];
+            const int piece = it * kWave + lane;     // 4-token piece index inside the chunk
+            stage[(piece / NIT) * kPitch + piece % NIT] = cw[it];
         }
-        pos[j] = group_start;
+        wave_lds_order();
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const uint4 x = stage[lane * kPitch + i];
+            w[4 * i] = x.x; w[4 * i + 1] = x.y; w[4 * i + 2] = x.z; w[4 * i + 3] = x.w;
+        }
     }
 }
 
-template <int G, bool PAGED>
+// The lowest `take` set bits of x.
+__device__ __forceinline__ unsigned lowest_bits(unsigned x, int take)
+{
+    unsigned r = 0;
+    for (int i = 0; i < take && x; ++i) {
+        const unsigned low = x & (0u - x);
+        r |= low;
+        x ^= low;
+    }
+    return r;
+}
+
+// Token ids of the set bits of m (bit p = token t0 + p), written to out[rank], out[rank + 1], ...
+__device__ __forceinline__ void emit_ids(unsigned m, int rank, int t0, int k_max, int32_t* __restrict__ out)
+{
+    while (__builtin_amdgcn_ballot_w64(m != 0u) != 0ull) {
+        if (m != 0u) {
+            if (rank < k_max) out[rank] = t0 + __builtin_ctz(m);
+            ++rank;
+            m &= m - 1u;
+        }
+    }
+}
+
+// NIT: 16-byte loads per lane and chunk (unit_tokens = 256 NIT for NIT < 4); NCH: chunks of 1024
+// tokens per unit (unit_tokens = 1024 NCH, NIT = 4).
+template <int G, bool PAGED, int NIT, int NCH>
 __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const uint32_t* __restrict__ q_codes,
                                                                const int32_t* __restrict__ k_per_seq, int k_max,
-                                                               int n_q_heads, int n_cap, int unit_tokens,
-                                                               int blocks_pitch, const int32_t* __restrict__ blk_cum,
-                                                               const uint16_t* __restrict__ unit_cum,
+                                                               int n_q_heads, int n_cap, int blocks_pitch,
+                                                               const int32_t* __restrict__ blk_cum,
                                                                int32_t* __restrict__ idx, int32_t* __restrict__ count,
                                                                uint8_t* __restrict__ threshold)
 {
+    constexpr int kTpl = 4 * NIT;                              // tokens per lane and chunk
+    constexpr int kChunkTokens = kTpl * kWave;
+    constexpr int kUnitTokens = kChunkTokens * NCH;
+    constexpr int kBlockTokens = kUnitTokens * kWpb;
     constexpr int kRowsPerPass = kThreads / kCumRow;           // 30 table rows are read side by side
+    constexpr int kPairs = (G + 1) / 2;                        // two heads share a packed wave sum / scan
+    extern __shared__ uint4 stage_all[];                       // NIT > 1: 64 * (NIT + 1) slots per wave
     __shared__ int tot[G * kCumRow];
-    __shared__ int2 upos[kWpb][G];                             // per wave and head: {first output slot, tie quota}
-    __shared__ int thr[G];
+    __shared__ int thr[G], posb[G], quotab[G];                 // per head: T, first output slot and tie quota of the block
+    __shared__ int wcnt[kWpb][kPairs], weq[kWpb][kPairs];      // per wave: selected / tied tokens, two heads per int
     const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int bx = rotated_block(blockIdx.x, kvh + b, gridDim.x);      // block index inside the sequence
-    const int unit0 = bx * kWpb, unit = unit0 + wave;
     const int64_t bh0 = (int64_t)b * n_q_heads + kvh * G;
     const int nb_cap = gridDim.x;                              // blocks the host launched per sequence
 
@@ -284,15 +261,16 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
 
     const int n = min(n_raw, n_cap);
     const int k = max(0, min(k_raw, min(k_max, n)));
-    const int block_tokens = kWpb * unit_tokens;
-    if (bx > 0 && ((int64_t)bx * block_tokens >= n || k == 0)) return;   // block 0 reports the counts
-    const int n_blocks = (n + block_tokens - 1) / block_tokens;
-    const int n_units = (n + unit_tokens - 1) / unit_tokens;
-    const int64_t t_begin = (int64_t)unit * unit_tokens;
+    if (bx > 0 && ((int64_t)bx * kBlockTokens >= n || k == 0)) return;   // block 0 reports the counts
+    const int n_blocks = (n + kBlockTokens - 1) / kBlockTokens;
+    const int64_t t_begin = ((int64_t)bx * kWpb + wave) * kUnitTokens;
     const bool active = t_begin < n && k > 0;
-    const int t_end = (int)min((int64_t)n, t_begin + unit_tokens);
-    uint4 cw[4];
-    if (active) load_chunk<PAGED>(c, b, kvh, (int)t_begin, t_end, lane, cw);
+    const int t_end = (int)min((int64_t)n, t_begin + kUnitTokens);
+    uint4 cw[NCH][NIT];
+    if (active) {
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) load_chunk<PAGED, NIT>(c, b, kvh, (int)t_begin + ch * kChunkTokens, t_end, lane, cw[ch]);
+    }
     __syncthreads();
 
     // ---- whole-sequence cumulative counts per head: sum of the per-block rows (stale rows of blocks
@@ -311,13 +289,12 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
     }
     __syncthreads();
 
-    // ---- selection parameters: wave j works them out for head j and for the 16 units of the block
+    // ---- selection parameters: wave j works them out for head j
     for (int j = wave; j < G; j += kWpb) {
         const int64_t bh = bh0 + j;
         const int32_t* tab = blk_cum + bh * blocks_pitch * kCumRow;
-        const uint16_t* utab = unit_cum + bh * blocks_pitch * kWpb * kCumRow;
         const int cum = lane < kCumRow ? tot[j * kCumRow + lane] : 0;   // #{score >= lane} over the sequence
-        int T = kBins, r = 0, gt = 0, ge = 0, ugt = 0, uge = 0;
+        int T = kBins, r = 0, gt = 0, ge = 0, own_gt = 0, own_ge = 0;
         if (k > 0) {
             const uint64_t ge_k = __ballot(lane < kBins && cum >= k);   // lane 0 is set: cum(0) = n >= k
             T = 63 - __clzll((long long)(ge_k | 1ull));
@@ -326,22 +303,17 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
                 ge += tab[blk * kCumRow + T];
                 gt += tab[blk * kCumRow + T + 1];
             }
-            if (lane < kWpb && unit0 + lane < n_units) {
-                uge = utab[(int64_t)(unit0 + lane) * kCumRow + T];
-                ugt = utab[(int64_t)(unit0 + lane) * kCumRow + T + 1];
-            }
+            own_ge = tab[bx * kCumRow + T];
+            own_gt = tab[bx * kCumRow + T + 1];
         }
-        gt = wave_sum_i32(gt);
+        gt = wave_sum_i32(gt);                                          // #{score > T} before this block
         ge = wave_sum_i32(ge);
-        const int ueq = uge - ugt;
-        const int gt_start = gt + wave_incl_scan_i32(ugt) - ugt;        // #{score > T} before unit `lane`
-        const int eq_start = (ge - gt) + wave_incl_scan_i32(ueq) - ueq; // #{score == T} before unit `lane`
-        if (lane < kWpb) {
-            const int left = r - eq_start;                              // tie quota still open at this unit
-            upos[lane][j] = make_int2(gt_start + min(eq_start, r), left >= ueq ? kAllTies : max(left, 0));
-        }
         if (lane == 0) {
+            const int eq_before = ge - gt, own_eq = own_ge - own_gt;    // #{score == T} before / inside this block
+            const int left = r - eq_before;                             // tie quota still open at this block
             thr[j] = T;
+            posb[j] = gt + min(eq_before, r);
+            quotab[j] = left >= own_eq ? kAllTies : max(left, 0);
             if (bx == 0) {
                 count[bh] = k;
                 if (threshold) threshold[bh] = (uint8_t)(k > 0 ? T : 0);
@@ -349,77 +321,204 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
         }
     }
     __syncthreads();
-    if (!active) return;
 
-    // ---- compaction of this wave's unit
-    int lim[G], pos[G], quota[G], ties_seen[G];
+    // ---- every wave: masks of the tokens to take (score > T, or >= T where the whole block's ties
+    // fit the quota) and, for a head whose quota ends inside this block, of its ties
+    uint4* stage = stage_all + wave * (kWave * (NIT + 1));
+    unsigned sel[NCH][G], tie[NCH][G];
+    int lim[G], quota[G];
+    bool any_partial = false;
 #pragma unroll
     for (int j = 0; j < G; ++j) {
         const int T = uniform(thr[j]);
-        const int2 u = upos[wave][j];
-        pos[j] = uniform(u.x);
-        quota[j] = uniform(u.y);
-        // score >= T (all ties taken) or score > T, as a bound on the Hamming distance 32 - score
-        lim[j] = quota[j] == kAllTies ? kBits - T : kBits - T - 1;
-        ties_seen[j] = 0;
+        quota[j] = uniform(quotab[j]);
+        lim[j] = quota[j] == kAllTies ? kBits - T : kBits - T - 1;      // bound on the Hamming distance 32 - score
+        any_partial |= quota[j] != kAllTies && quota[j] != 0;
     }
-    for (int base = (int)t_begin; base < t_end; base += kChunk) {
-        if (base != (int)t_begin) load_chunk<PAGED>(c, b, kvh, base, t_end, lane, cw);
-        const int groups = (min(t_end - base, kChunk) + 4 * kWave - 1) / (4 * kWave);     // uniform over the wave
-        int32_t* idx0 = idx + bh0 * k_max;
-        if (groups == 1)
-            compact_chunk<G, 1>(cw, base, t_end, lane, qc, lim, quota, pos, ties_seen, idx0, k_max);
-        else if (groups == 2)
-            compact_chunk<G, 2>(cw, base, t_end, lane, qc, lim, quota, pos, ties_seen, idx0, k_max);
-        else
-            compact_chunk<G, 4>(cw, base, t_end, lane, qc, lim, quota, pos, ties_seen, idx0, k_max);
+    int csum[kPairs], esum[kPairs];
+#pragma unroll
+    for (int pr = 0; pr < kPairs; ++pr) csum[pr] = esum[pr] = 0;
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+#pragma unroll
+        for (int j = 0; j < G; ++j) sel[ch][j] = tie[ch][j] = 0u;
+        const int cbase = (int)t_begin + ch * kChunkTokens;
+        if (active && cbase < t_end) {                                  // uniform over the wave
+            uint32_t w[kTpl];
+            to_lane_runs<NIT>(cw[ch], stage, lane, w);
+            const int n_valid = max(0, min(t_end - (cbase + lane * kTpl), kTpl));   // of this lane's run
+            const unsigned valid = (1u << n_valid) - 1u;
+#pragma unroll
+            for (int j = 0; j < G; ++j) {
+                sel[ch][j] = within_mask<kTpl>(w, qc[j], lim[j]) & valid;
+                if (any_partial && quota[j] != kAllTies && quota[j] != 0)
+                    tie[ch][j] = equal_mask<kTpl>(w, qc[j], lim[j] + 1) & valid;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            csum[j >> 1] += __popc(sel[ch][j]) << (16 * (j & 1));
+            esum[j >> 1] += __popc(tie[ch][j]) << (16 * (j & 1));
+        }
+    }
+#pragma unroll
+    for (int pr = 0; pr < kPairs; ++pr) {
+        const int cs = wave_sum_i32(csum[pr]);
+        const int es = any_partial ? wave_sum_i32(esum[pr]) : 0;
+        if (lane == 0) { wcnt[wave][pr] = cs; weq[wave][pr] = es; }
+    }
+    __syncthreads();
+    if (!active) return;
+
+    // ---- first output slot of this wave per head; resolve a quota that ends inside the block
+    int start[G];
+#pragma unroll
+    for (int pr = 0; pr < kPairs; ++pr) {
+        const int before2 = wave_sum_i32(lane < wave ? wcnt[lane][pr] : 0);
+        const int eqb2 = any_partial ? wave_sum_i32(lane < wave ? weq[lane][pr] : 0) : 0;
+        const int own2 = any_partial ? weq[wave][pr] : 0;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int j = 2 * pr + h;
+            if (j >= G) break;
+            const int before = (before2 >> (16 * h)) & 0xffff;
+            start[j] = uniform(posb[j]) + before;
+            if (quota[j] != kAllTies && quota[j] != 0) {
+                const int eq_before = (eqb2 >> (16 * h)) & 0xffff, own = (own2 >> (16 * h)) & 0xffff;
+                const int left = quota[j] - eq_before;                  // quota still open at this wave
+                start[j] += min(eq_before, quota[j]);
+                if (left >= own) {
+#pragma unroll
+                    for (int ch = 0; ch < NCH; ++ch) sel[ch][j] |= tie[ch][j];
+                } else if (left > 0) {                                  // ties are ranked in token order
+                    int seen = 0;
+#pragma unroll
+                    for (int ch = 0; ch < NCH; ++ch) {
+                        const int mine = __popc(tie[ch][j]);
+                        const int incl = wave_incl_scan_i32(mine);
+                        const int take = max(0, min(mine, left - seen - (incl - mine)));
+                        sel[ch][j] |= lowest_bits(tie[ch][j], take);
+                        seen += __builtin_amdgcn_readlane(incl, 63);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- ranks in token order and the ids
+    int32_t* idx0 = idx + bh0 * k_max;
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+        const int first = (int)t_begin + ch * kChunkTokens + lane * kTpl;
+#pragma unroll
+        for (int pr = 0; pr < kPairs; ++pr) {
+            const int j0 = 2 * pr, j1 = 2 * pr + 1;
+            const int c0 = __popc(sel[ch][j0]), c1 = j1 < G ? __popc(sel[ch][j1 < G ? j1 : j0]) : 0;
+            const int incl = wave_incl_scan_i32(c0 | (c1 << 16));
+            const int total = __builtin_amdgcn_readlane(incl, 63);
+            emit_ids(sel[ch][j0], start[j0] + (incl & 0xffff) - c0, first, k_max, idx0 + (int64_t)j0 * k_max);
+            start[j0] += total & 0xffff;
+            if (j1 < G) {
+                const int jj = j1 < G ? j1 : j0;
+                emit_ids(sel[ch][jj], start[jj] + (int)((unsigned)incl >> 16) - c1, first, k_max, idx0 + (int64_t)jj * k_max);
+                start[jj] += (int)((unsigned)total >> 16);
+            }
+        }
+    }
+}
+
+template <int G, bool PAGED, int NIT, int NCH>
+hipError_t select_variant(bool setup_only, const KvView& kv, const uint32_t* q_codes, const int32_t* k_per_seq, int k_max,
+                          int n_q_heads, int max_seq_len, const TopkScratch& sc, int32_t* idx, int32_t* count,
+                          uint8_t* threshold, dim3 grid, hipStream_t stream)
+{
+    constexpr int lds = NIT > 1 ? kWpb * kWave * (NIT + 1) * (int)sizeof(uint4) : 0;
+    if (setup_only)
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_select_kernel<G, PAGED, NIT, NCH>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    topk_select_kernel<G, PAGED, NIT, NCH><<<grid, dim3(kThreads), lds, stream>>>(
+        kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc.blocks_pitch, sc.blk_cum, idx, count, threshold);
+    return hipSuccess;
+}
+
+template <int G, bool PAGED>
+hipError_t select_by_unit(bool setup_only, int unit_tokens, const KvView& kv, const uint32_t* q_codes,
+                          const int32_t* k_per_seq, int k_max, int n_q_heads, int max_seq_len, const TopkScratch& sc,
+                          int32_t* idx, int32_t* count, uint8_t* threshold, dim3 grid, hipStream_t stream)
+{
+    switch (unit_tokens) {
+    case 256: return select_variant<G, PAGED, 1, 1>(setup_only, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, grid, stream);
+    case 512: return select_variant<G, PAGED, 2, 1>(setup_only, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, grid, stream);
+    case 1024: return select_variant<G, PAGED, 4, 1>(setup_only, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, grid, stream);
+    case 2048: return select_variant<G, PAGED, 4, 2>(setup_only, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, grid, stream);
+    default: return hipErrorInvalidValue;
     }
 }
 
 template <int G>
-hipError_t launch_g(const KvView& kv, bool paged, const uint32_t* q_codes, int batch, int n_q_heads,
+hipError_t launch_g(bool setup_only, const KvView& kv, bool paged, const uint32_t* q_codes, int batch, int n_q_heads,
                     const int32_t* k_per_seq, int k_max, int max_seq_len, int unit_tokens,
                     const TopkScratch& sc, int32_t* idx, int32_t* count, uint8_t* threshold,
                     hipStream_t stream)
 {
+    if (setup_only) {
+        for (int unit = 256; unit <= 2048; unit *= 2) {
+            hipError_t e = select_by_unit<G, false>(true, unit, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, dim3(1), stream);
+            if (e == hipSuccess) e = select_by_unit<G, true>(true, unit, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, dim3(1), stream);
+            if (e != hipSuccess) return e;
+        }
+        return hipSuccess;
+    }
     const int64_t block_tokens = (int64_t)kWpb * unit_tokens;
     int n_blocks = (int)((max_seq_len + block_tokens - 1) / block_tokens);
     if (n_blocks < 1) n_blocks = 1;               // block 0 of every group still reports count = 0
     const dim3 grid(n_blocks, kv.n_kv_heads, batch), block(kThreads);
+    hipError_t e;
     if (paged) {
         score_hist_kernel<G, true><<<grid, block, 0, stream>>>(kv, q_codes, n_q_heads, max_seq_len, unit_tokens,
-                                                                sc.blocks_pitch, sc.blk_cum, sc.unit_cum);
-        topk_select_kernel<G, true><<<grid, block, 0, stream>>>(kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len,
-                                                                 unit_tokens, sc.blocks_pitch, sc.blk_cum, sc.unit_cum, idx, count,
-                                                                 threshold);
+                                                                sc.blocks_pitch, sc.blk_cum);
+        e = select_by_unit<G, true>(false, unit_tokens, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, grid, stream);
     } else {
         score_hist_kernel<G, false><<<grid, block, 0, stream>>>(kv, q_codes, n_q_heads, max_seq_len, unit_tokens,
-                                                                 sc.blocks_pitch, sc.blk_cum, sc.unit_cum);
-        topk_select_kernel<G, false><<<grid, block, 0, stream>>>(kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len,
-                                                                  unit_tokens, sc.blocks_pitch, sc.blk_cum, sc.unit_cum, idx, count,
-                                                                  threshold);
+                                                                 sc.blocks_pitch, sc.blk_cum);
+        e = select_by_unit<G, false>(false, unit_tokens, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, grid, stream);
     }
+    if (e != hipSuccess) return e;
     return hipGetLastError();
 }
 
+hipError_t dispatch_group(bool setup_only, const KvView& kv, bool paged, int group, const uint32_t* q_codes,
+                          int batch, int n_q_heads, const int32_t* k_per_seq, int k_max,
+                          int max_seq_len, int unit_tokens, const TopkScratch& sc,
+                          int32_t* idx, int32_t* count, uint8_t* threshold, hipStream_t stream)
+{
+    switch (group) {
+    case 1: return launch_g<1>(setup_only, kv, paged, q_codes, batch, n_q_heads, k_per_seq, k_max, max_seq_len, unit_tokens, sc, idx, count, threshold, stream);
+    case 2: return launch_g<2>(setup_only, kv, paged, q_codes, batch, n_q_heads, k_per_seq, k_max, max_seq_len, unit_tokens, sc, idx, count, threshold, stream);
+    case 4: return launch_g<4>(setup_only, kv, paged, q_codes, batch, n_q_heads, k_per_seq, k_max, max_seq_len, unit_tokens, sc, idx, count, threshold, stream);
+    case 8: return launch_g<8>(setup_only, kv, paged, q_codes, batch, n_q_heads, k_per_seq, k_max, max_seq_len, unit_tokens, sc, idx, count, threshold, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
 }  // namespace
+
+// Raises the dynamic LDS limit of the select kernels of this group size (their staging area passes
+// 64 KiB); called once when a context is created, never on the launch path.
+hipError_t setup_score_topk(int group)
+{
+    const KvView none{};
+    const TopkScratch sc{};
+    return dispatch_group(true, none, false, group, nullptr, 0, 0, nullptr, 0, 0, 0, sc, nullptr, nullptr, nullptr, nullptr);
+}
 
 hipError_t launch_score_topk(const KvView& kv, bool paged, int group, const uint32_t* q_codes,
                              int batch, int n_q_heads, const int32_t* k_per_seq, int k_max,
                              int max_seq_len, int unit_tokens, const TopkScratch& sc,
                              int32_t* idx, int32_t* count, uint8_t* threshold, hipStream_t stream)
 {
-    switch (group) {
-    case 1: return launch_g<1>(kv, paged, q_codes, batch, n_q_heads, k_per_seq, k_max, max_seq_len,
-                               unit_tokens, sc, idx, count, threshold, stream);
-    case 2: return launch_g<2>(kv, paged, q_codes, batch, n_q_heads, k_per_seq, k_max, max_seq_len,
-                               unit_tokens, sc, idx, count, threshold, stream);
-    case 4: return launch_g<4>(kv, paged, q_codes, batch, n_q_heads, k_per_seq, k_max, max_seq_len,
-                               unit_tokens, sc, idx, count, threshold, stream);
-    case 8: return launch_g<8>(kv, paged, q_codes, batch, n_q_heads, k_per_seq, k_max, max_seq_len,
-                               unit_tokens, sc, idx, count, threshold, stream);
-    default: return hipErrorInvalidValue;
-    }
+    return dispatch_group(false, kv, paged, group, q_codes, batch, n_q_heads, k_per_seq, k_max, max_seq_len,
+                          unit_tokens, sc, idx, count, threshold, stream);
 }
 
 }  // namespace ha
