@@ -137,14 +137,21 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
     }
 }
 
-// Bit p of the result: token p of the lane has Hamming distance <= lim (or == dist) to qc.
+// Bit p of the result (p < TPL): token p of the lane has Hamming distance <= lim to qc; the bits from
+// TPL up are set.  popcount + bias has its top bit set exactly when the distance exceeds lim, and
+// one funnel shift moves that bit into the mask: three instructions per token and head.
 template <int TPL>
 __device__ __forceinline__ unsigned within_mask(const uint32_t (&w)[TPL], uint32_t qc, int lim)
 {
+    const unsigned bias = 0x7fffffffu - (unsigned)lim;       // lim is in -2..32
     unsigned m = 0;
 #pragma unroll
-    for (int p = TPL - 1; p >= 0; --p) m = (m << 1) | (unsigned)((int)__popc(w[p] ^ qc) <= lim);
-    return m;
+    for (int p = TPL - 1; p >= 0; --p) {
+        unsigned d;                                          // popcount(w ^ qc) + bias in one instruction
+        asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(d) : "v"(w[p] ^ qc), "s"(bias));
+        m = __builtin_amdgcn_alignbit(m, d, 31);             // (m << 1) | top bit of d
+    }
+    return ~m;
 }
 
 template <int TPL>
