@@ -86,14 +86,20 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int bx = rotated_block(blockIdx.x, kvh + b, gridDim.x);      // block index inside the sequence
     const int unit = bx * kWpb + wave;
+    const int64_t t_begin = (int64_t)unit * unit_tokens;
+    uint4 cw[4];
+    // contiguous cache: rows up to the host's bound n_cap exist whatever the sequence length is, so
+    // the first loads need not wait for it (what lies past the length is masked out below)
+    if constexpr (!PAGED) {
+        if (t_begin < n_cap) load_chunk<PAGED, 4>(c, b, kvh, (int)t_begin, (int)min((int64_t)n_cap, t_begin + unit_tokens), lane, cw);
+    }
     const int n = min(c.seq_lens[b], n_cap);   // n_cap: the host's bound that sized grid and scratch
     if ((int64_t)bx * kWpb * unit_tokens >= n) return;      // whole block beyond the sequence
-    const int64_t t_begin = (int64_t)unit * unit_tokens;
     const bool active = t_begin < n;
     const int t_end = (int)min((int64_t)n, t_begin + unit_tokens);
-
-    uint4 cw[4];
-    if (active) load_chunk<PAGED, 4>(c, b, kvh, (int)t_begin, t_end, lane, cw);
+    if constexpr (PAGED) {
+        if (active) load_chunk<PAGED, 4>(c, b, kvh, (int)t_begin, t_end, lane, cw);
+    }
     uint32_t qc[G];
 #pragma unroll
     for (int j = 0; j < G; ++j) qc[j] = (uint32_t)uniform((int)q_codes[(int64_t)b * n_q_heads + kvh * G + j]);
@@ -147,8 +153,8 @@ __device__ __forceinline__ unsigned within_mask(const uint32_t (&w)[TPL], uint32
     unsigned m = 0;
 #pragma unroll
     for (int p = TPL - 1; p >= 0; --p) {
-        unsigned d;                                          // popcount(w ^ qc) + bias in one instruction
-        asm("v_bcnt_u32_b32 %0, %1, %2" : "=v"(d) : "v"(w[p] ^ qc), "s"(bias));
+        unsigned d;                                          // popcount(w ^ qc) + bias: the count instruction adds its second operand
+        asm("v_xor_b32 %0, %2, %1\n\tv_bcnt_u32_b32 %0, %0, %3" : "=&v"(d) : "v"(w[p]), "s"(qc), "s"(bias));
         m = __builtin_amdgcn_alignbit(m, d, 31);             // (m << 1) | top bit of d
     }
     return ~m;
@@ -173,25 +179,23 @@ __device__ __forceinline__ void wave_lds_order()
 }
 
 // From the coalesced load layout to runs: afterwards lane L holds tokens base + L * TPL .. + TPL - 1
-// (TPL = 4 NIT) in w.  `stage` is the wave's own LDS area of 64 * (NIT + 1) 16-byte slots; the odd
-// pitch keeps the 16-byte reads of neighbouring lanes on different banks.
+// (TPL = 4 NIT) in w.  `stage` is the wave's own LDS area of 64 * NIT 16-byte slots.
 template <int NIT>
 __device__ __forceinline__ void to_lane_runs(const uint4 (&cw)[NIT], uint4* stage, int lane, uint32_t (&w)[NIT * 4])
 {
     if constexpr (NIT == 1) {
         w[0] = cw[0].x; w[1] = cw[0].y; w[2] = cw[0].z; w[3] = cw[0].w;
     } else {
-        constexpr int kPitch = NIT + 1;
         wave_lds_order();                            // earlier reads of the area are done
 #pragma unroll
         for (int it = 0; it < NIT; ++it) {
             const int piece = it * kWave + lane;     // 4-token piece index inside the chunk
-            stage[(piece / NIT) * kPitch + piece % NIT] = cw[it];
+            stage[piece] = cw[it];              // piece p of the chunk belongs to lane p / NIT
         }
         wave_lds_order();
 #pragma unroll
         for (int i = 0; i < NIT; ++i) {
-            const uint4 x = stage[lane * kPitch + i];
+            const uint4 x = stage[lane * NIT + i];
             w[4 * i] = x.x; w[4 * i + 1] = x.y; w[4 * i + 2] = x.z; w[4 * i + 3] = x.w;
         }
     }
@@ -237,7 +241,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
     constexpr int kBlockTokens = kUnitTokens * kWpb;
     constexpr int kRowsPerPass = kThreads / kCumRow;           // 30 table rows are read side by side
     constexpr int kPairs = (G + 1) / 2;                        // two heads share a packed wave sum / scan
-    extern __shared__ uint4 stage_all[];                       // NIT > 1: 64 * (NIT + 1) slots per wave
+    extern __shared__ uint4 stage_all[];                       // NIT > 1: 64 * NIT slots per wave
     __shared__ int tot[G * kCumRow];
     __shared__ int thr[G], posb[G], quotab[G];                 // per head: T, first output slot and tie quota of the block
     __shared__ int wcnt[kWpb][kPairs], weq[kWpb][kPairs];      // per wave: selected / tied tokens, two heads per int
@@ -261,6 +265,10 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
             if (srow < kRowsPerPass && blk < nb_cap)
                 tv[j][u] = blk_cum[((bh0 + j) * blocks_pitch + blk) * kCumRow + scol];
         }
+    const int64_t t_begin = ((int64_t)bx * kWpb + wave) * kUnitTokens;
+    uint4 cw[NIT];
+    if constexpr (!PAGED)            // contiguous cache: no need to wait for the sequence length (see score_hist)
+        load_chunk<PAGED, NIT>(c, b, kvh, (int)t_begin, (int)min((int64_t)n_cap, t_begin + kUnitTokens), lane, cw);
     uint32_t qc[G];
 #pragma unroll
     for (int j = 0; j < G; ++j) qc[j] = (uint32_t)uniform((int)q_codes[bh0 + j]);
@@ -270,13 +278,10 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
     const int k = max(0, min(k_raw, min(k_max, n)));
     if (bx > 0 && ((int64_t)bx * kBlockTokens >= n || k == 0)) return;   // block 0 reports the counts
     const int n_blocks = (n + kBlockTokens - 1) / kBlockTokens;
-    const int64_t t_begin = ((int64_t)bx * kWpb + wave) * kUnitTokens;
     const bool active = t_begin < n && k > 0;
     const int t_end = (int)min((int64_t)n, t_begin + kUnitTokens);
-    uint4 cw[NCH][NIT];
-    if (active) {
-#pragma unroll
-        for (int ch = 0; ch < NCH; ++ch) load_chunk<PAGED, NIT>(c, b, kvh, (int)t_begin + ch * kChunkTokens, t_end, lane, cw[ch]);
+    if constexpr (PAGED) {
+        if (active) load_chunk<PAGED, NIT>(c, b, kvh, (int)t_begin, t_end, lane, cw);
     }
     __syncthreads();
 
@@ -331,7 +336,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
 
     // ---- every wave: masks of the tokens to take (score > T, or >= T where the whole block's ties
     // fit the quota) and, for a head whose quota ends inside this block, of its ties
-    uint4* stage = stage_all + wave * (kWave * (NIT + 1));
+    uint4* stage = stage_all + wave * (kWave * NIT);
     unsigned sel[NCH][G], tie[NCH][G];
     int lim[G], quota[G];
     bool any_partial = false;
@@ -352,7 +357,9 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
         const int cbase = (int)t_begin + ch * kChunkTokens;
         if (active && cbase < t_end) {                                  // uniform over the wave
             uint32_t w[kTpl];
-            to_lane_runs<NIT>(cw[ch], stage, lane, w);
+            to_lane_runs<NIT>(cw, stage, lane, w);
+            if (ch + 1 < NCH && cbase + kChunkTokens < t_end)           // next chunk: on its way while this one is scored
+                load_chunk<PAGED, NIT>(c, b, kvh, cbase + kChunkTokens, t_end, lane, cw);
             const int n_valid = max(0, min(t_end - (cbase + lane * kTpl), kTpl));   // of this lane's run
             const unsigned valid = (1u << n_valid) - 1u;
 #pragma unroll
@@ -439,7 +446,7 @@ hipError_t select_variant(bool setup_only, const KvView& kv, const uint32_t* q_c
                           int n_q_heads, int max_seq_len, const TopkScratch& sc, int32_t* idx, int32_t* count,
                           uint8_t* threshold, dim3 grid, hipStream_t stream)
 {
-    constexpr int lds = NIT > 1 ? kWpb * kWave * (NIT + 1) * (int)sizeof(uint4) : 0;
+    constexpr int lds = NIT > 1 ? kWpb * kWave * NIT * (int)sizeof(uint4) : 0;
     if (setup_only)
         return hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_select_kernel<G, PAGED, NIT, NCH>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds);
