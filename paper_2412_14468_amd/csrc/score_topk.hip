@@ -41,15 +41,18 @@ constexpr int kWpb = kTopkWavesPerBlock;
 constexpr int kThreads = kWpb * kWave;
 
 // NIT 16-byte loads per lane, coalesced: load `it` of lane L holds tokens base + it * 256 + 4 L .. + 3.
+// Needs base < t_end.  Pieces past t_end repeat the last piece before it instead of being skipped
+// (callers mask by token index), so the loads are unconditional and the compiler can wait for them
+// one by one.
 template <bool PAGED, int NIT>
 __device__ __forceinline__ void load_chunk(const KvView& c, int b, int kvh, int base, int t_end, int lane,
                                            uint4 (&cw)[NIT])
 {
+    const int last = (t_end - 1) & ~3;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-        const int t0 = base + it * 4 * kWave + lane * 4;
-        cw[it] = make_uint4(0u, 0u, 0u, 0u);
-        if (t0 < t_end) cw[it] = *reinterpret_cast<const uint4*>(c.codes + row_of<PAGED>(c, b, kvh, t0));
+        const int t0 = min(base + it * 4 * kWave + lane * 4, last);
+        cw[it] = *reinterpret_cast<const uint4*>(c.codes + row_of<PAGED>(c, b, kvh, t0));
     }
 }
 
@@ -82,18 +85,26 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
 {
     __shared__ __attribute__((aligned(16))) unsigned hist[G * kBins * kBinCopies];   // [head][score][copy]
     __shared__ int bsum[G * kBins];
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, wave = uniform(tid >> 6), lane = tid & 63;    // wave: scalar, so are the token ranges
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int bx = rotated_block(blockIdx.x, kvh + b, gridDim.x);      // block index inside the sequence
     const int unit = bx * kWpb + wave;
     const int64_t t_begin = (int64_t)unit * unit_tokens;
+    // loads complete in issue order: the few small ones go first, so that waiting for them does not
+    // mean waiting for the codes
+    int qraw[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) qraw[j] = (int)q_codes[(int64_t)b * n_q_heads + kvh * G + j];
+    const int n_raw = c.seq_lens[b];
     uint4 cw[4];
+#pragma unroll
+    for (int it = 0; it < 4; ++it) cw[it] = make_uint4(0u, 0u, 0u, 0u);     // element by element: keeps the array in registers
     // contiguous cache: rows up to the host's bound n_cap exist whatever the sequence length is, so
     // the first loads need not wait for it (what lies past the length is masked out below)
     if constexpr (!PAGED) {
         if (t_begin < n_cap) load_chunk<PAGED, 4>(c, b, kvh, (int)t_begin, (int)min((int64_t)n_cap, t_begin + unit_tokens), lane, cw);
     }
-    const int n = min(c.seq_lens[b], n_cap);   // n_cap: the host's bound that sized grid and scratch
+    const int n = min(n_raw, n_cap);           // n_cap: the host's bound that sized grid and scratch
     if ((int64_t)bx * kWpb * unit_tokens >= n) return;      // whole block beyond the sequence
     const bool active = t_begin < n;
     const int t_end = (int)min((int64_t)n, t_begin + unit_tokens);
@@ -102,7 +113,7 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
     }
     uint32_t qc[G];
 #pragma unroll
-    for (int j = 0; j < G; ++j) qc[j] = (uint32_t)uniform((int)q_codes[(int64_t)b * n_q_heads + kvh * G + j]);
+    for (int j = 0; j < G; ++j) qc[j] = (uint32_t)uniform(qraw[j]);
     for (int i = tid; i < G * kBins * kBinCopies; i += kThreads) hist[i] = 0u;
     __syncthreads();
 
@@ -245,7 +256,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
     __shared__ int tot[G * kCumRow];
     __shared__ int thr[G], posb[G], quotab[G];                 // per head: T, first output slot and tie quota of the block
     __shared__ int wcnt[kWpb][kPairs], weq[kWpb][kPairs];      // per wave: selected / tied tokens, two heads per int
-    const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+    const int tid = threadIdx.x, wave = uniform(tid >> 6), lane = tid & 63;    // wave: scalar, so are the token ranges
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int bx = rotated_block(blockIdx.x, kvh + b, gridDim.x);      // block index inside the sequence
     const int64_t bh0 = (int64_t)b * n_q_heads + kvh * G;
@@ -265,13 +276,20 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
             if (srow < kRowsPerPass && blk < nb_cap)
                 tv[j][u] = blk_cum[((bh0 + j) * blocks_pitch + blk) * kCumRow + scol];
         }
+    int qraw[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) qraw[j] = (int)q_codes[bh0 + j];
+    // the codes go last: loads complete in issue order, and nothing before the scoring needs them
     const int64_t t_begin = ((int64_t)bx * kWpb + wave) * kUnitTokens;
     uint4 cw[NIT];
-    if constexpr (!PAGED)            // contiguous cache: no need to wait for the sequence length (see score_hist)
-        load_chunk<PAGED, NIT>(c, b, kvh, (int)t_begin, (int)min((int64_t)n_cap, t_begin + kUnitTokens), lane, cw);
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) cw[it] = make_uint4(0u, 0u, 0u, 0u);   // element by element: keeps the array in registers
+    if constexpr (!PAGED) {          // contiguous cache: no need to wait for the sequence length (see score_hist)
+        if (t_begin < n_cap) load_chunk<PAGED, NIT>(c, b, kvh, (int)t_begin, (int)min((int64_t)n_cap, t_begin + kUnitTokens), lane, cw);
+    }
     uint32_t qc[G];
 #pragma unroll
-    for (int j = 0; j < G; ++j) qc[j] = (uint32_t)uniform((int)q_codes[bh0 + j]);
+    for (int j = 0; j < G; ++j) qc[j] = (uint32_t)uniform(qraw[j]);
     for (int i = tid; i < G * kCumRow; i += kThreads) tot[i] = 0;
 
     const int n = min(n_raw, n_cap);
