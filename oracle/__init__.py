@@ -59,6 +59,14 @@ def lib():
                                             C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                             C.c_void_p, C.c_int64, C.c_double, C.c_void_p,
                                             C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ha_oracle_topk_window.restype = C.c_int64
+        L.ha_oracle_topk_window.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int64,
+                                            C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ha_oracle_decode_step_window.restype = None
+        L.ha_oracle_decode_step_window.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                                   C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                                   C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_double,
+                                                   C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -208,6 +216,19 @@ def topk_hist(sc: np.ndarray, k: int):
     return _topk(lib().ha_oracle_topk_hist, sc, k)
 
 
+def topk_window(sc: np.ndarray, k: int, n_sink: int, n_local: int):
+    """TOPK with the first n_sink and last n_local tokens always kept; k counts only the tokens
+    retrieved besides them.  Returns (idx ascending, threshold, number retrieved)."""
+    sc = _chk(np.ascontiguousarray(sc), np.int32)
+    n = sc.shape[0]
+    idx = np.zeros(max(n, 1), dtype=np.int32)
+    thr = C.c_int32(0)
+    got = C.c_int64(0)
+    cnt = lib().ha_oracle_topk_window(sc.ctypes.data, n, k, n_sink, n_local, idx.ctypes.data,
+                                      C.byref(thr), C.byref(got))
+    return idx[:cnt].copy(), int(thr.value), int(got.value)
+
+
 # ------------------------------------------------------------------ attention
 def gather_attend(cache: Cache, b: int, h_kv: int, q_bf16: np.ndarray, idx: np.ndarray,
                   scale: float) -> np.ndarray:
@@ -230,11 +251,14 @@ def dense_attend(cache: Cache, b: int, h_kv: int, q_bf16: np.ndarray, n: int, sc
 # ------------------------------------------------------------------ whole step
 def decode_step(phi_q: Optional[Mlp], phi_kv: Optional[Mlp], cache: Cache, q_bf16: np.ndarray,
                 k_per_seq: np.ndarray, scale: float, k_new: Optional[np.ndarray] = None,
-                v_new: Optional[np.ndarray] = None, q_codes: Optional[np.ndarray] = None):
+                v_new: Optional[np.ndarray] = None, q_codes: Optional[np.ndarray] = None,
+                n_sink: int = 0, n_local: int = 0):
     """One layer decode step for every (sequence, query head).
 
-    Returns dict(q_codes [B,Hq], idx [B,Hq,k_max], count [B,Hq], threshold [B,Hq], out [B,Hq,d] f64).
+    Returns dict(q_codes [B,Hq], idx [B,Hq,pitch], count [B,Hq], threshold [B,Hq], out [B,Hq,d] f64).
     With phi_q None the given q_codes are used.  k_new/v_new [B,Hkv,d] are appended first.
+    n_sink / n_local > 0: the first / most recent tokens are always kept and k counts only the
+    retrieved ones (pitch = k_max + n_sink + n_local); otherwise pitch = k_max.
     """
     q = _chk(np.ascontiguousarray(q_bf16), np.uint16)
     B, Hq, d = q.shape
@@ -247,10 +271,19 @@ def decode_step(phi_q: Optional[Mlp], phi_kv: Optional[Mlp], cache: Cache, q_bf1
     if k_new is not None:
         k_new = _chk(np.ascontiguousarray(k_new), np.uint16)
         v_new = _chk(np.ascontiguousarray(v_new), np.uint16)
-    idx = np.full((B, Hq, k_max), -1, dtype=np.int32)
+    window = n_sink > 0 or n_local > 0
+    idx = np.full((B, Hq, k_max + n_sink + n_local), -1, dtype=np.int32)
     count = np.zeros((B, Hq), dtype=np.int32)
     thr = np.zeros((B, Hq), dtype=np.int32)
     out = np.zeros((B, Hq, d), dtype=np.float64)
+    if window:
+        lib().ha_oracle_decode_step_window(None if phi_q is None else C.addressof(phi_q.c),
+                                           None if phi_kv is None else C.addressof(phi_kv.c),
+                                           C.addressof(cache.c), q.ctypes.data, _ptr(k_new), _ptr(v_new),
+                                           B, Hq, kps.ctypes.data, k_max, n_sink, n_local, float(scale),
+                                           qc.ctypes.data, idx.ctypes.data, count.ctypes.data,
+                                           thr.ctypes.data, out.ctypes.data)
+        return dict(q_codes=qc, idx=idx, count=count, threshold=thr, out=out)
     lib().ha_oracle_decode_step(None if phi_q is None else C.addressof(phi_q.c),
                                 None if phi_kv is None else C.addressof(phi_kv.c),
                                 C.addressof(cache.c), q.ctypes.data, _ptr(k_new), _ptr(v_new),

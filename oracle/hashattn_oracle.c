@@ -7,7 +7,8 @@
  *   - SCORE    Hamming distance as bitcount(xor) (section 4.1, eq. 1 and the
  *              "Implementation" paragraph); used as the similarity 32 - H,
  *              which orders tokens exactly as -H does
- *   - TOPK     "standard top-k on these scores" (section 4)
+ *   - TOPK     "standard top-k on these scores" (section 4); optionally with the first and most
+ *              recent tokens always kept and the budget counting only retrieved tokens (section 5)
  *   - GATHER-ATT  softmax attention restricted to the index set (section 4)
  *   - SDPA     single-query dense attention (section 3.1)
  * All floating point is fp64.  No blocking, no fusion, no vectorisation.
@@ -232,6 +233,33 @@ int64_t ha_oracle_topk_hist(const int32_t* scores, int64_t n, int64_t k, int32_t
     return out;
 }
 
+/* TOPK with the always-kept tokens of the evaluation protocol (section 5, "Baselines and setup"):
+ * the first n_sink and the most recent n_local tokens are in the index set whatever they score, and
+ * the budget k counts only the tokens retrieved besides them.  Written out:
+ *   I = {0 .. lo-1}  u  lo + topk(scores[lo .. hi-1], k)  u  {hi .. n-1},
+ *   lo = min(n_sink, n),  hi = max(lo, n - n_local),
+ * ascending by index.  Returns |I|; *threshold gets the smallest retrieved score (0 when nothing is
+ * retrieved), *n_retrieved the number of retrieved tokens. */
+int64_t ha_oracle_topk_window(const int32_t* scores, int64_t n, int64_t k, int64_t n_sink, int64_t n_local,
+                              int32_t* idx, int32_t* threshold, int64_t* n_retrieved)
+{
+    if (n < 0) n = 0;
+    int64_t lo = n_sink < n ? n_sink : n;
+    if (lo < 0) lo = 0;
+    int64_t hi = n - (n_local > 0 ? n_local : 0);
+    if (hi < lo) hi = lo;
+    int64_t out = 0;
+    for (int64_t t = 0; t < lo; ++t) idx[out++] = (int32_t)t;
+    int32_t T = 0;
+    int64_t got = ha_oracle_topk_sort(scores + lo, hi - lo, k, idx + out, &T);
+    for (int64_t i = 0; i < got; ++i) idx[out + i] += (int32_t)lo;      /* back to token ids of the sequence */
+    out += got;
+    for (int64_t t = hi; t < n; ++t) idx[out++] = (int32_t)t;
+    if (threshold) *threshold = got > 0 ? T : 0;
+    if (n_retrieved) *n_retrieved = got;
+    return out;
+}
+
 /* ------------------------------------------------ GATHER-ATT and SDPA (sections 3.1, 4) */
 
 /* o = sum_{i in I} softmax_i(scale <q, k_i>) v_i over the rows listed in idx (logical token ids
@@ -303,6 +331,36 @@ void ha_oracle_decode_step(const ha_mlp* phi_q, const ha_mlp* phi_kv, ha_cache* 
         count[bh] = (int32_t)cnt;
         threshold[bh] = T;
         ha_oracle_gather_attend(c, b, hk, qv, idx + bh * k_max, cnt, scale, out + bh * d);
+        free(scores);
+    }
+}
+
+/* The same step with the always-kept window of ha_oracle_topk_window.  idx rows have
+ * pitch = k_max + n_sink + n_local entries; count is the size of the whole index set. */
+void ha_oracle_decode_step_window(const ha_mlp* phi_q, const ha_mlp* phi_kv, ha_cache* c,
+                                  const uint16_t* q, const uint16_t* k_new, const uint16_t* v_new,
+                                  int batch, int n_q_heads, const int32_t* k_per_seq, int64_t k_max,
+                                  int64_t n_sink, int64_t n_local,
+                                  double scale, uint32_t* q_codes, int32_t* idx, int32_t* count,
+                                  int32_t* threshold, double* out)
+{
+    int d = c->head_dim, Hq = n_q_heads, g = Hq / c->n_kv_heads;
+    int64_t pitch = k_max + n_sink + n_local;
+    if (k_new) ha_oracle_encode_keys(phi_kv, c, k_new, v_new, batch, 1, NULL);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t bh = 0; bh < (int64_t)batch * Hq; ++bh) {
+        int b = (int)(bh / Hq), h = (int)(bh % Hq), hk = h / g;
+        int64_t n = c->seq_lens[b];
+        const uint16_t* qv = q + bh * d;
+        if (phi_q) q_codes[bh] = ha_oracle_encode_vec(phi_q, h, qv, NULL);   /* else: given */
+        int32_t* scores = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+        for (int64_t t = 0; t < n; ++t)
+            scores[t] = ha_oracle_score(q_codes[bh], c->codes[row_of(c, b, hk, t)]);
+        int32_t T = 0;
+        int64_t cnt = ha_oracle_topk_window(scores, n, k_per_seq[b], n_sink, n_local, idx + bh * pitch, &T, NULL);
+        count[bh] = (int32_t)cnt;
+        threshold[bh] = T;
+        ha_oracle_gather_attend(c, b, hk, qv, idx + bh * pitch, cnt, scale, out + bh * d);
         free(scores);
     }
 }
