@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--sink", type=int, default=0, help="always keep this many first tokens (k counts the rest)")
+    ap.add_argument("--local", type=int, default=0, help="always keep this many most recent tokens")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     return ap.parse_args()
@@ -165,8 +167,10 @@ def main():
         layers.append(device_layer_synthetic(cfg, W.BASE_SEED + 1000 * cfg.index + len(layers), torch))
     n_cap = max(int(s.k.shape[2]) if s.page_table is None else int(s.page_table.shape[1]) * cfg.page_size for s in layers)
     k_max = max(s.k_max for s in layers)
-    ctx = ha.Context(Hq, Hkv, B, n_cap, k_max, page_size=cfg.page_size)
+    ctx = ha.Context(Hq, Hkv, B, n_cap, k_max + args.sink + args.local, page_size=cfg.page_size)
     for s in layers:
+        if args.sink or args.local:
+            s.set_window(args.sink, args.local)
         runner.build_key_codes(ctx, s)
         s.lens0_dev = s.seq_lens.clone()
         s.max_len0 = s.cache.max_seq_len
@@ -210,6 +214,12 @@ def main():
     us_per_step = seconds * 1e6 / K
     lens_final = [int(n) + (1 if cfg.append else 0) for n in layers[0].lens_host]
     ks = [int(x) for x in layers[0].k_host]
+    if args.sink or args.local:          # tokens attended per head: always-kept ones plus the retrieved budget
+        def attended(n, kk):
+            lo = min(args.sink, n)
+            hi = max(lo, n - args.local)
+            return lo + min(kk, hi - lo) + (n - hi)
+        ks = [attended(n, kk) for n, kk in zip(lens_final, ks)]
     alg_bytes = W.algorithmic_bytes(Hkv, Hq, d, lens_final, ks)
     gbs = alg_bytes / (us_per_step * 1e-6) / 1e9
     k = k_max
@@ -217,7 +227,7 @@ def main():
     # ---- dominant kernel (GATHER-ATT) by HIP events on its own graph of `ring` launches
     def gather_sweep():
         for s in layers:
-            ctx.hashattn_gather_attend(s.q, s.cache, s.idx, s.count, s.B, s.k_max, s.scale, s.out)
+            runner.gather_attend(ctx, s)
     gather_bytes = W.gathered_bytes(Hq, d, lens_final, ks)
     if args.no_graph:
         gather_us = event_time_us(torch, gather_sweep, 10) / ring
@@ -236,7 +246,7 @@ def main():
 
     def topk_sweep():
         for s in layers:
-            ctx.hashattn_score_topk(s.q_codes, s.cache, s.B, s.k_per_seq, s.k_max, s.idx, s.count, s.threshold)
+            runner.score_topk(ctx, s)
 
     def encq_sweep():
         for s in layers:
@@ -269,7 +279,7 @@ def main():
         t_all = time.perf_counter()
         while len(times) < 3 or (time.perf_counter() - t_all < 10.0 and len(times) < 40):
             t0 = time.perf_counter()
-            res = oracle.decode_step(phi_q, phi_kv, ocache, L0.q, L0.k_per_seq, scale)
+            res = oracle.decode_step(phi_q, phi_kv, ocache, L0.q, L0.k_per_seq, scale, n_sink=args.sink, n_local=args.local)
             times.append(time.perf_counter() - t0)
         cpu_s = float(np.median(times))
         cpu = {"value": round(alg_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "us_per_layer_step": round(cpu_s * 1e6, 1),
@@ -280,7 +290,9 @@ def main():
         runner.decode_step(ctx, s0)
         torch.cuda.synchronize()
         got = s0.out.float().cpu().numpy().astype(np.float64)
-        same_sets = bool(np.array_equal(s0.idx.cpu().numpy()[:, :, :k], res["idx"]))
+        n_att = int(res["count"].max())
+        same_sets = bool(np.array_equal(s0.count.cpu().numpy(), res["count"]) and
+                         np.array_equal(s0.idx.cpu().numpy()[:, :, :n_att], res["idx"][:, :, :n_att]))
         err = np.abs(got - res["out"])
         parity = {"index_sets_equal": same_sets,
                   "out_within_tol": bool(np.all(err <= 2e-3 + 1e-2 * np.abs(res["out"]))) if same_sets else None,
@@ -295,7 +307,9 @@ def main():
                                f"k={describe_lengths(ks)} ({round(sum(lens_final) / max(sum(ks), 1))}x sparsity), "
                                f"{Hq} q heads / {Hkv} KV heads, d={d}, mapping MLPs {'-'.join(map(str, cfg.mlp_dims))} fp32"
                                + (", paged KV (16 tokens/page)" if cfg.page_size else "")
-                               + (", one-token append per step" if cfg.append else ""),
+                               + (", one-token append per step" if cfg.append else "")
+                               + (f", first {args.sink} and last {args.local} tokens always kept (k counts them here)"
+                                  if args.sink or args.local else ""),
                    "batch": B, "context": max(lens_final), "k": k, "ring_layers": ring, "launch": launch,
                    "algorithmic_bytes_per_step": alg_bytes},
         "roofline": {"bound": "hbm", "kernel": "hashattn_gather_attend = gather_attend_kernel + merge_partials_kernel",

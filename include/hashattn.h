@@ -140,6 +140,25 @@ hashattn_status hashattn_score_topk(hashattn_ctx* ctx, const uint32_t* q_codes,
                                     int32_t* idx, int32_t* count, uint8_t* threshold,
                                     void* stream);
 
+/* SCORE + TOPK with always-kept tokens (section 5, "Baselines and setup": the
+ * first and the most recent tokens are always in context and the token budget
+ * counts only the tokens retrieved besides them).  With lo = min(n_sink, N) and
+ * hi = max(lo, N - n_local), N = seq_lens[b], the index set of (b, h) is
+ *   {0 .. lo-1}  u  the min(k_b, hi - lo) best tokens of [lo, hi)  u  {hi .. N-1},
+ * ascending; the always-kept tokens are not scored.  n_sink = n_local = 0 is
+ * hashattn_score_topk.  Arguments as there, except:
+ *   n_sink, n_local  host, >= 0; k_max + n_sink + n_local <= max_k
+ *   idx        dev int32 [batch][n_q_heads][k_max + n_sink + n_local]
+ *   count      lo + min(k_b, hi - lo) + (N - hi)
+ *   threshold  smallest retrieved score (0 when nothing is retrieved)
+ * Pass k_max + n_sink + n_local as k_max to hashattn_gather_attend. */
+hashattn_status hashattn_score_topk_window(hashattn_ctx* ctx, const uint32_t* q_codes,
+                                           const hashattn_kv* cache, int32_t batch,
+                                           const int32_t* k_per_seq, int32_t k_max,
+                                           int32_t n_sink, int32_t n_local,
+                                           int32_t* idx, int32_t* count, uint8_t* threshold,
+                                           void* stream);
+
 /* GATHER-ATT (section 4): softmax attention over the selected tokens only,
  *   out[b][h] = sum_{i in I} softmax_i(scale * <q, k_i>) v_i,
  * normalised over the selected tokens, fp32 accumulation, bf16 result.

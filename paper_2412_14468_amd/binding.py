@@ -72,6 +72,8 @@ def load() -> C.CDLL:
     L.hashattn_encode_query.argtypes = [vp, C.POINTER(MlpStruct), vp, i32, vp, vp]
     L.hashattn_score_topk.restype = i32
     L.hashattn_score_topk.argtypes = [vp, vp, C.POINTER(KvStruct), i32, vp, i32, vp, vp, vp, vp]
+    L.hashattn_score_topk_window.restype = i32
+    L.hashattn_score_topk_window.argtypes = [vp, vp, C.POINTER(KvStruct), i32, vp, i32, i32, i32, vp, vp, vp, vp]
     L.hashattn_gather_attend.restype = i32
     L.hashattn_gather_attend.argtypes = [vp, vp, C.POINTER(KvStruct), vp, vp, i32, i32, C.c_float, vp, vp]
     L.hashattn_dense_attend.restype = i32
@@ -190,6 +192,12 @@ class Context:
                             threshold=None, stream=None) -> None:
         self._check(load().hashattn_score_topk(self.h, _ptr(q_codes), C.byref(cache.c), batch, _ptr(k_per_seq),
                                                k_max, _ptr(idx), _ptr(count), _ptr(threshold), _stream(stream)))
+
+    def hashattn_score_topk_window(self, q_codes, cache: KvCache, batch: int, k_per_seq, k_max: int, n_sink: int,
+                                   n_local: int, idx, count, threshold=None, stream=None) -> None:
+        self._check(load().hashattn_score_topk_window(self.h, _ptr(q_codes), C.byref(cache.c), batch,
+                                                      _ptr(k_per_seq), k_max, n_sink, n_local, _ptr(idx),
+                                                      _ptr(count), _ptr(threshold), _stream(stream)))
 
     def hashattn_gather_attend(self, q, cache: KvCache, idx, count, batch: int, k_max: int, scale: float, out,
                                stream=None) -> None:

@@ -281,9 +281,10 @@ hashattn_status hashattn_encode_query(hashattn_ctx* ctx, const hashattn_mlp* phi
     return e == hipSuccess ? HASHATTN_OK : hip_fail(ctx, e, "encode_query");
 }
 
-hashattn_status hashattn_score_topk(hashattn_ctx* ctx, const uint32_t* q_codes, const hashattn_kv* cache,
-                                    int32_t batch, const int32_t* k_per_seq, int32_t k_max, int32_t* idx,
-                                    int32_t* count, uint8_t* threshold, void* stream)
+hashattn_status hashattn_score_topk_window(hashattn_ctx* ctx, const uint32_t* q_codes, const hashattn_kv* cache,
+                                           int32_t batch, const int32_t* k_per_seq, int32_t k_max, int32_t n_sink,
+                                           int32_t n_local, int32_t* idx, int32_t* count, uint8_t* threshold,
+                                           void* stream)
 {
     if (!ctx) return HASHATTN_INVALID_ARG;
     if (hashattn_status s = check_cache(ctx, cache, batch, true, "score_topk")) return s;
@@ -291,13 +292,24 @@ hashattn_status hashattn_score_topk(hashattn_ctx* ctx, const uint32_t* q_codes, 
     if (!aligned(q_codes, 4) || !aligned(idx, 4) || !aligned(count, 4) || (k_per_seq && !aligned(k_per_seq, 4)))
         return fail(ctx, HASHATTN_INVALID_ARG, "score_topk: 4-byte alignment required");
     if (k_max < 1) return fail(ctx, HASHATTN_INVALID_ARG, "score_topk: k_max %d < 1", k_max);
-    if (k_max > ctx->cfg.max_k) return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "score_topk: k_max %d exceeds max_k %lld", k_max, (long long)ctx->cfg.max_k);
+    if (n_sink < 0 || n_local < 0) return fail(ctx, HASHATTN_INVALID_ARG, "score_topk: n_sink %d or n_local %d is negative", n_sink, n_local);
+    if ((int64_t)k_max + n_sink + n_local > ctx->cfg.max_k)
+        return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "score_topk: k_max + n_sink + n_local = %lld exceeds max_k %lld",
+                    (long long)k_max + n_sink + n_local, (long long)ctx->cfg.max_k);
     const ha::TopkScratch sc{ctx->blk_cum, ctx->blocks_pitch};
     const int unit = pick_unit_tokens(ctx, batch, cache->max_seq_len, k_per_seq != nullptr);
-    const hipError_t e = ha::launch_score_topk(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group, q_codes, batch,
-                                               ctx->cfg.n_q_heads, k_per_seq, k_max, cache->max_seq_len, unit, sc,
-                                               idx, count, threshold, static_cast<hipStream_t>(stream));
+    const ha::TopkCall call{q_codes, k_per_seq, k_max, n_sink, n_local, batch, ctx->cfg.n_q_heads, cache->max_seq_len,
+                            idx, count, threshold};
+    const hipError_t e = ha::launch_score_topk(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group, call, unit, sc,
+                                               static_cast<hipStream_t>(stream));
     return e == hipSuccess ? HASHATTN_OK : hip_fail(ctx, e, "score_topk");
+}
+
+hashattn_status hashattn_score_topk(hashattn_ctx* ctx, const uint32_t* q_codes, const hashattn_kv* cache,
+                                    int32_t batch, const int32_t* k_per_seq, int32_t k_max, int32_t* idx,
+                                    int32_t* count, uint8_t* threshold, void* stream)
+{
+    return hashattn_score_topk_window(ctx, q_codes, cache, batch, k_per_seq, k_max, 0, 0, idx, count, threshold, stream);
 }
 
 hashattn_status hashattn_gather_attend(hashattn_ctx* ctx, const void* q, const hashattn_kv* cache, const int32_t* idx,

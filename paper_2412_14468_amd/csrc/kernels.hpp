@@ -27,10 +27,21 @@ hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
 
 hipError_t setup_score_topk(int group);
 
-hipError_t launch_score_topk(const KvView& kv, bool paged, int group, const uint32_t* q_codes,
-                             int batch, int n_q_heads, const int32_t* k_per_seq, int k_max,
-                             int max_seq_len, int unit_tokens, const TopkScratch& sc,
-                             int32_t* idx, int32_t* count, uint8_t* threshold, hipStream_t stream);
+// Arguments of one SCORE + TOPK call.  The first n_sink and the last n_local tokens of every sequence
+// are always selected; k counts the tokens retrieved between them; idx rows have
+// k_max + n_sink + n_local entries.
+struct TopkCall {
+    const uint32_t* q_codes;
+    const int32_t* k_per_seq;
+    int32_t k_max, n_sink, n_local;
+    int32_t batch, n_q_heads, max_seq_len;
+    int32_t* idx;
+    int32_t* count;
+    uint8_t* threshold;
+};
+
+hipError_t launch_score_topk(const KvView& kv, bool paged, int group, const TopkCall& call, int unit_tokens,
+                             const TopkScratch& sc, hipStream_t stream);
 
 hipError_t launch_gather_attend(const KvView& kv, bool paged, int group, const uint16_t* q,
                                 const int32_t* idx, const int32_t* count, int batch, int n_q_heads,

@@ -56,8 +56,9 @@ __device__ __forceinline__ void load_chunk(const KvView& c, int b, int kvh, int 
     }
 }
 
+// CHECKED: only tokens t with lo <= t < hi are counted.
 template <int G, bool CHECKED>
-__device__ __forceinline__ void count_chunk(const uint4 (&cw)[4], int base, int t_end, int lane,
+__device__ __forceinline__ void count_chunk(const uint4 (&cw)[4], int base, int lo, int hi, int lane,
                                             const uint32_t (&qc)[G], unsigned* mine)
 {
 #pragma unroll
@@ -66,7 +67,7 @@ __device__ __forceinline__ void count_chunk(const uint4 (&cw)[4], int base, int 
         const uint32_t w[4] = {cw[it].x, cw[it].y, cw[it].z, cw[it].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            if (!CHECKED || t0 + e < t_end) {
+            if (!CHECKED || (t0 + e >= lo && t0 + e < hi)) {
 #pragma unroll
                 for (int j = 0; j < G; ++j)       // score = popcount of the agreeing bits
                     atomicAdd(&mine[(j * kBins + __popc(~(w[e] ^ qc[j]))) * kBinCopies], 1u);
@@ -81,6 +82,7 @@ __device__ __forceinline__ void count_chunk(const uint4 (&cw)[4], int base, int 
 template <int G, bool PAGED>
 __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const uint32_t* __restrict__ q_codes,
                                                               int n_q_heads, int n_cap, int unit_tokens,
+                                                              int n_sink, int n_local,
                                                               int blocks_pitch, int32_t* __restrict__ blk_cum)
 {
     __shared__ __attribute__((aligned(16))) unsigned hist[G * kBins * kBinCopies];   // [head][score][copy]
@@ -108,6 +110,7 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
     if ((int64_t)bx * kWpb * unit_tokens >= n) return;      // whole block beyond the sequence
     const bool active = t_begin < n;
     const int t_end = (int)min((int64_t)n, t_begin + unit_tokens);
+    const int lo = min(n_sink, n), hi = max(lo, n - n_local);   // always-kept tokens [0, lo) and [hi, n) are not scored
     if constexpr (PAGED) {
         if (active) load_chunk<PAGED, 4>(c, b, kvh, (int)t_begin, t_end, lane, cw);
     }
@@ -123,8 +126,8 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
             uint4 nx[4];
             const bool more = base + kChunk < t_end;
             if (more) load_chunk<PAGED, 4>(c, b, kvh, base + kChunk, t_end, lane, nx);
-            if (base + kChunk <= t_end) count_chunk<G, false>(cw, base, t_end, lane, qc, mine);
-            else count_chunk<G, true>(cw, base, t_end, lane, qc, mine);     // ragged end of the sequence
+            if (base >= lo && base + kChunk <= min(t_end, hi)) count_chunk<G, false>(cw, base, lo, hi, lane, qc, mine);
+            else count_chunk<G, true>(cw, base, lo, min(t_end, hi), lane, qc, mine);   // ragged end, window edges
             if (more) {
 #pragma unroll
                 for (int it = 0; it < 4; ++it) cw[it] = nx[it];
@@ -225,11 +228,11 @@ __device__ __forceinline__ unsigned lowest_bits(unsigned x, int take)
 }
 
 // Token ids of the set bits of m (bit p = token t0 + p), written to out[rank], out[rank + 1], ...
-__device__ __forceinline__ void emit_ids(unsigned m, int rank, int t0, int k_max, int32_t* __restrict__ out)
+__device__ __forceinline__ void emit_ids(unsigned m, int rank, int t0, int pitch, int32_t* __restrict__ out)
 {
     while (__builtin_amdgcn_ballot_w64(m != 0u) != 0ull) {
         if (m != 0u) {
-            if (rank < k_max) out[rank] = t0 + __builtin_ctz(m);
+            if (rank < pitch) out[rank] = t0 + __builtin_ctz(m);
             ++rank;
             m &= m - 1u;
         }
@@ -241,6 +244,7 @@ __device__ __forceinline__ void emit_ids(unsigned m, int rank, int t0, int k_max
 template <int G, bool PAGED, int NIT, int NCH>
 __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const uint32_t* __restrict__ q_codes,
                                                                const int32_t* __restrict__ k_per_seq, int k_max,
+                                                               int n_sink, int n_local, int pitch,
                                                                int n_q_heads, int n_cap, int blocks_pitch,
                                                                const int32_t* __restrict__ blk_cum,
                                                                int32_t* __restrict__ idx, int32_t* __restrict__ count,
@@ -293,10 +297,13 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
     for (int i = tid; i < G * kCumRow; i += kThreads) tot[i] = 0;
 
     const int n = min(n_raw, n_cap);
-    const int k = max(0, min(k_raw, min(k_max, n)));
-    if (bx > 0 && ((int64_t)bx * kBlockTokens >= n || k == 0)) return;   // block 0 reports the counts
+    // the first `lo` and the tokens from `hi` on are always taken; k counts the tokens retrieved in between
+    const int lo = min(n_sink, n), hi = max(lo, n - n_local);
+    const int k = max(0, min(k_raw, min(k_max, hi - lo)));
+    const bool nothing = k == 0 && lo == 0 && hi == n;
+    if (bx > 0 && ((int64_t)bx * kBlockTokens >= n || nothing)) return;   // block 0 reports the counts
     const int n_blocks = (n + kBlockTokens - 1) / kBlockTokens;
-    const bool active = t_begin < n && k > 0;
+    const bool active = t_begin < n && !nothing;
     const int t_end = (int)min((int64_t)n, t_begin + kUnitTokens);
     if constexpr (PAGED) {
         if (active) load_chunk<PAGED, NIT>(c, b, kvh, (int)t_begin, t_end, lane, cw);
@@ -341,11 +348,12 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
         if (lane == 0) {
             const int eq_before = ge - gt, own_eq = own_ge - own_gt;    // #{score == T} before / inside this block
             const int left = r - eq_before;                             // tie quota still open at this block
+            const int bs = (int)min((int64_t)n, (int64_t)bx * kBlockTokens);   // always-kept tokens before this block
             thr[j] = T;
-            posb[j] = gt + min(eq_before, r);
+            posb[j] = gt + min(eq_before, r) + min(lo, bs) + max(0, bs - hi);
             quotab[j] = left >= own_eq ? kAllTies : max(left, 0);
             if (bx == 0) {
-                count[bh] = k;
+                count[bh] = lo + k + (n - hi);
                 if (threshold) threshold[bh] = (uint8_t)(k > 0 ? T : 0);
             }
         }
@@ -378,13 +386,16 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
             to_lane_runs<NIT>(cw, stage, lane, w);
             if (ch + 1 < NCH && cbase + kChunkTokens < t_end)           // next chunk: on its way while this one is scored
                 load_chunk<PAGED, NIT>(c, b, kvh, cbase + kChunkTokens, t_end, lane, cw);
-            const int n_valid = max(0, min(t_end - (cbase + lane * kTpl), kTpl));   // of this lane's run
-            const unsigned valid = (1u << n_valid) - 1u;
+            const int first = cbase + lane * kTpl;                          // first token of this lane's run
+            auto below = [&](int t) { return (1u << max(0, min(t - first, kTpl))) - 1u; };   // bits of tokens < t
+            const unsigned valid = below(t_end);
+            const unsigned scored = below(hi) & ~below(lo) & valid;         // tokens that compete for the budget
+            const unsigned kept = valid & ~scored;                          // always-kept tokens
 #pragma unroll
             for (int j = 0; j < G; ++j) {
-                sel[ch][j] = within_mask<kTpl>(w, qc[j], lim[j]) & valid;
+                sel[ch][j] = (within_mask<kTpl>(w, qc[j], lim[j]) & scored) | kept;
                 if (any_partial && quota[j] != kAllTies && quota[j] != 0)
-                    tie[ch][j] = equal_mask<kTpl>(w, qc[j], lim[j] + 1) & valid;
+                    tie[ch][j] = equal_mask<kTpl>(w, qc[j], lim[j] + 1) & scored;
             }
         }
 #pragma unroll
@@ -438,7 +449,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
     }
 
     // ---- ranks in token order and the ids
-    int32_t* idx0 = idx + bh0 * k_max;
+    int32_t* idx0 = idx + bh0 * pitch;
 #pragma unroll
     for (int ch = 0; ch < NCH; ++ch) {
         const int first = (int)t_begin + ch * kChunkTokens + lane * kTpl;
@@ -448,11 +459,11 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
             const int c0 = __popc(sel[ch][j0]), c1 = j1 < G ? __popc(sel[ch][j1 < G ? j1 : j0]) : 0;
             const int incl = wave_incl_scan_i32(c0 | (c1 << 16));
             const int total = __builtin_amdgcn_readlane(incl, 63);
-            emit_ids(sel[ch][j0], start[j0] + (incl & 0xffff) - c0, first, k_max, idx0 + (int64_t)j0 * k_max);
+            emit_ids(sel[ch][j0], start[j0] + (incl & 0xffff) - c0, first, pitch, idx0 + (int64_t)j0 * pitch);
             start[j0] += total & 0xffff;
             if (j1 < G) {
                 const int jj = j1 < G ? j1 : j0;
-                emit_ids(sel[ch][jj], start[jj] + (int)((unsigned)incl >> 16) - c1, first, k_max, idx0 + (int64_t)jj * k_max);
+                emit_ids(sel[ch][jj], start[jj] + (int)((unsigned)incl >> 16) - c1, first, pitch, idx0 + (int64_t)jj * pitch);
                 start[jj] += (int)((unsigned)total >> 16);
             }
         }
@@ -460,97 +471,88 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
 }
 
 template <int G, bool PAGED, int NIT, int NCH>
-hipError_t select_variant(bool setup_only, const KvView& kv, const uint32_t* q_codes, const int32_t* k_per_seq, int k_max,
-                          int n_q_heads, int max_seq_len, const TopkScratch& sc, int32_t* idx, int32_t* count,
-                          uint8_t* threshold, dim3 grid, hipStream_t stream)
+hipError_t select_variant(bool setup_only, const KvView& kv, const TopkCall& a, const TopkScratch& sc, dim3 grid,
+                          hipStream_t stream)
 {
     constexpr int lds = NIT > 1 ? kWpb * kWave * NIT * (int)sizeof(uint4) : 0;
     if (setup_only)
         return hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_select_kernel<G, PAGED, NIT, NCH>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     topk_select_kernel<G, PAGED, NIT, NCH><<<grid, dim3(kThreads), lds, stream>>>(
-        kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc.blocks_pitch, sc.blk_cum, idx, count, threshold);
+        kv, a.q_codes, a.k_per_seq, a.k_max, a.n_sink, a.n_local, a.k_max + a.n_sink + a.n_local, a.n_q_heads,
+        a.max_seq_len, sc.blocks_pitch, sc.blk_cum, a.idx, a.count, a.threshold);
     return hipSuccess;
 }
 
 template <int G, bool PAGED>
-hipError_t select_by_unit(bool setup_only, int unit_tokens, const KvView& kv, const uint32_t* q_codes,
-                          const int32_t* k_per_seq, int k_max, int n_q_heads, int max_seq_len, const TopkScratch& sc,
-                          int32_t* idx, int32_t* count, uint8_t* threshold, dim3 grid, hipStream_t stream)
+hipError_t select_by_unit(bool setup_only, int unit_tokens, const KvView& kv, const TopkCall& a, const TopkScratch& sc,
+                          dim3 grid, hipStream_t stream)
 {
     switch (unit_tokens) {
-    case 256: return select_variant<G, PAGED, 1, 1>(setup_only, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, grid, stream);
-    case 512: return select_variant<G, PAGED, 2, 1>(setup_only, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, grid, stream);
-    case 1024: return select_variant<G, PAGED, 4, 1>(setup_only, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, grid, stream);
-    case 2048: return select_variant<G, PAGED, 4, 2>(setup_only, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, grid, stream);
+    case 256: return select_variant<G, PAGED, 1, 1>(setup_only, kv, a, sc, grid, stream);
+    case 512: return select_variant<G, PAGED, 2, 1>(setup_only, kv, a, sc, grid, stream);
+    case 1024: return select_variant<G, PAGED, 4, 1>(setup_only, kv, a, sc, grid, stream);
+    case 2048: return select_variant<G, PAGED, 4, 2>(setup_only, kv, a, sc, grid, stream);
     default: return hipErrorInvalidValue;
     }
 }
 
-template <int G>
-hipError_t launch_g(bool setup_only, const KvView& kv, bool paged, const uint32_t* q_codes, int batch, int n_q_heads,
-                    const int32_t* k_per_seq, int k_max, int max_seq_len, int unit_tokens,
-                    const TopkScratch& sc, int32_t* idx, int32_t* count, uint8_t* threshold,
-                    hipStream_t stream)
+template <int G, bool PAGED>
+hipError_t launch_gp(bool setup_only, const KvView& kv, const TopkCall& a, int unit_tokens, const TopkScratch& sc,
+                     hipStream_t stream)
 {
     if (setup_only) {
-        for (int unit = 256; unit <= 2048; unit *= 2) {
-            hipError_t e = select_by_unit<G, false>(true, unit, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, dim3(1), stream);
-            if (e == hipSuccess) e = select_by_unit<G, true>(true, unit, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, dim3(1), stream);
-            if (e != hipSuccess) return e;
-        }
+        for (int unit = 256; unit <= 2048; unit *= 2)
+            if (hipError_t e = select_by_unit<G, PAGED>(true, unit, kv, a, sc, dim3(1), stream); e != hipSuccess) return e;
         return hipSuccess;
     }
     const int64_t block_tokens = (int64_t)kWpb * unit_tokens;
-    int n_blocks = (int)((max_seq_len + block_tokens - 1) / block_tokens);
+    int n_blocks = (int)((a.max_seq_len + block_tokens - 1) / block_tokens);
     if (n_blocks < 1) n_blocks = 1;               // block 0 of every group still reports count = 0
-    const dim3 grid(n_blocks, kv.n_kv_heads, batch), block(kThreads);
-    hipError_t e;
-    if (paged) {
-        score_hist_kernel<G, true><<<grid, block, 0, stream>>>(kv, q_codes, n_q_heads, max_seq_len, unit_tokens,
-                                                                sc.blocks_pitch, sc.blk_cum);
-        e = select_by_unit<G, true>(false, unit_tokens, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, grid, stream);
-    } else {
-        score_hist_kernel<G, false><<<grid, block, 0, stream>>>(kv, q_codes, n_q_heads, max_seq_len, unit_tokens,
-                                                                 sc.blocks_pitch, sc.blk_cum);
-        e = select_by_unit<G, false>(false, unit_tokens, kv, q_codes, k_per_seq, k_max, n_q_heads, max_seq_len, sc, idx, count, threshold, grid, stream);
-    }
-    if (e != hipSuccess) return e;
+    const dim3 grid(n_blocks, kv.n_kv_heads, a.batch), block(kThreads);
+    score_hist_kernel<G, PAGED><<<grid, block, 0, stream>>>(kv, a.q_codes, a.n_q_heads, a.max_seq_len, unit_tokens,
+                                                             a.n_sink, a.n_local, sc.blocks_pitch, sc.blk_cum);
+    if (hipError_t e = select_by_unit<G, PAGED>(false, unit_tokens, kv, a, sc, grid, stream); e != hipSuccess) return e;
     return hipGetLastError();
 }
 
-hipError_t dispatch_group(bool setup_only, const KvView& kv, bool paged, int group, const uint32_t* q_codes,
-                          int batch, int n_q_heads, const int32_t* k_per_seq, int k_max,
-                          int max_seq_len, int unit_tokens, const TopkScratch& sc,
-                          int32_t* idx, int32_t* count, uint8_t* threshold, hipStream_t stream)
+template <int G>
+hipError_t launch_g(bool setup_only, const KvView& kv, bool paged, const TopkCall& a, int unit_tokens,
+                    const TopkScratch& sc, hipStream_t stream)
+{
+    if (setup_only) {
+        if (hipError_t e = launch_gp<G, false>(true, kv, a, unit_tokens, sc, stream); e != hipSuccess) return e;
+        return launch_gp<G, true>(true, kv, a, unit_tokens, sc, stream);
+    }
+    return paged ? launch_gp<G, true>(false, kv, a, unit_tokens, sc, stream)
+                 : launch_gp<G, false>(false, kv, a, unit_tokens, sc, stream);
+}
+
+hipError_t dispatch_group(bool setup_only, const KvView& kv, bool paged, int group, const TopkCall& a,
+                          int unit_tokens, const TopkScratch& sc, hipStream_t stream)
 {
     switch (group) {
-    case 1: return launch_g<1>(setup_only, kv, paged, q_codes, batch, n_q_heads, k_per_seq, k_max, max_seq_len, unit_tokens, sc, idx, count, threshold, stream);
-    case 2: return launch_g<2>(setup_only, kv, paged, q_codes, batch, n_q_heads, k_per_seq, k_max, max_seq_len, unit_tokens, sc, idx, count, threshold, stream);
-    case 4: return launch_g<4>(setup_only, kv, paged, q_codes, batch, n_q_heads, k_per_seq, k_max, max_seq_len, unit_tokens, sc, idx, count, threshold, stream);
-    case 8: return launch_g<8>(setup_only, kv, paged, q_codes, batch, n_q_heads, k_per_seq, k_max, max_seq_len, unit_tokens, sc, idx, count, threshold, stream);
+    case 1: return launch_g<1>(setup_only, kv, paged, a, unit_tokens, sc, stream);
+    case 2: return launch_g<2>(setup_only, kv, paged, a, unit_tokens, sc, stream);
+    case 4: return launch_g<4>(setup_only, kv, paged, a, unit_tokens, sc, stream);
+    case 8: return launch_g<8>(setup_only, kv, paged, a, unit_tokens, sc, stream);
     default: return hipErrorInvalidValue;
     }
 }
 
 }  // namespace
 
-// Raises the dynamic LDS limit of the select kernels of this group size (their staging area passes
+// Raises the dynamic LDS limit of the select kernels of this group size (their staging area reaches
 // 64 KiB); called once when a context is created, never on the launch path.
 hipError_t setup_score_topk(int group)
 {
-    const KvView none{};
-    const TopkScratch sc{};
-    return dispatch_group(true, none, false, group, nullptr, 0, 0, nullptr, 0, 0, 0, sc, nullptr, nullptr, nullptr, nullptr);
+    return dispatch_group(true, KvView{}, false, group, TopkCall{}, 0, TopkScratch{}, nullptr);
 }
 
-hipError_t launch_score_topk(const KvView& kv, bool paged, int group, const uint32_t* q_codes,
-                             int batch, int n_q_heads, const int32_t* k_per_seq, int k_max,
-                             int max_seq_len, int unit_tokens, const TopkScratch& sc,
-                             int32_t* idx, int32_t* count, uint8_t* threshold, hipStream_t stream)
+hipError_t launch_score_topk(const KvView& kv, bool paged, int group, const TopkCall& call, int unit_tokens,
+                             const TopkScratch& sc, hipStream_t stream)
 {
-    return dispatch_group(false, kv, paged, group, q_codes, batch, n_q_heads, k_per_seq, k_max, max_seq_len,
-                          unit_tokens, sc, idx, count, threshold, stream);
+    return dispatch_group(false, kv, paged, group, call, unit_tokens, sc, stream);
 }
 
 }  // namespace ha

@@ -36,6 +36,14 @@ class LayerState:
         self.out = torch.zeros((self.B, self.Hq, self.d), dtype=torch.bfloat16, device=dev)
         self.dense_out = torch.zeros_like(self.out)
         self.scale = 1.0 / math.sqrt(self.d)
+        self.n_sink = self.n_local = 0
+        self.pitch = self.k_max                      # entries per row of idx
+
+    def set_window(self, n_sink: int, n_local: int) -> None:
+        """Always keep the first n_sink and the most recent n_local tokens; k counts the rest."""
+        self.n_sink, self.n_local = int(n_sink), int(n_local)
+        self.pitch = self.k_max + self.n_sink + self.n_local
+        self.idx = torch.zeros((self.B, self.Hq, self.pitch), dtype=torch.int32, device=self.q.device)
 
 
 def layer_from_tensors(t: dict) -> LayerState:
@@ -57,8 +65,20 @@ def decode_step(ctx: Context, s: LayerState, append: bool = False) -> None:
         ctx.hashattn_encode_keys(s.phi_kv, s.k_new, s.v_new, s.B, 1, s.cache)
     if s.phi_q is not None:
         ctx.hashattn_encode_query(s.phi_q, s.q, s.B, s.q_codes)
-    ctx.hashattn_score_topk(s.q_codes, s.cache, s.B, s.k_per_seq, s.k_max, s.idx, s.count, s.threshold)
-    ctx.hashattn_gather_attend(s.q, s.cache, s.idx, s.count, s.B, s.k_max, s.scale, s.out)
+    score_topk(ctx, s)
+    gather_attend(ctx, s)
+
+
+def score_topk(ctx: Context, s: LayerState) -> None:
+    if s.n_sink or s.n_local:
+        ctx.hashattn_score_topk_window(s.q_codes, s.cache, s.B, s.k_per_seq, s.k_max, s.n_sink, s.n_local,
+                                       s.idx, s.count, s.threshold)
+    else:
+        ctx.hashattn_score_topk(s.q_codes, s.cache, s.B, s.k_per_seq, s.k_max, s.idx, s.count, s.threshold)
+
+
+def gather_attend(ctx: Context, s: LayerState) -> None:
+    ctx.hashattn_gather_attend(s.q, s.cache, s.idx, s.count, s.B, s.pitch, s.scale, s.out)
 
 
 def dense_step(ctx: Context, s: LayerState) -> None:
