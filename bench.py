@@ -253,6 +253,19 @@ def main():
             ctx.hashattn_encode_query(s.phi_q, s.q, s.B, s.q_codes)
     topk_us, encq_us = stage_us(topk_sweep), stage_us(encq_sweep)
 
+    # ---- prefill side: rebuilding the whole key-code store of one layer (not part of the decode step)
+    def rebuild():
+        runner.build_key_codes(ctx, layers[0])
+    rebuild()
+    enc_us = event_time_us(torch, rebuild, 3)
+    n_vec = sum(int(n) for n in layers[0].lens_host) * Hkv
+    dims = cfg.mlp_dims
+    mlp_flop = 2 * sum(a * b for a, b in zip(dims[:-1], dims[1:]))
+    key_encode = {"us": round(enc_us, 1), "Mvectors_per_s": round(n_vec / enc_us, 1),
+                  "algorithmic_TFLOPs": round(n_vec * mlp_flop / (enc_us * 1e-6) / 1e12, 1),
+                  "key_read_GBps": round(n_vec * d * 2 / (enc_us * 1e-6) / 1e9, 1),
+                  "note": "fp32-equivalent flops of the mapping; run as 2-3 bf16 MFMA passes per layer"}
+
     # ---- in-house dense decode on the same ring
     dense = None
     if not args.no_dense:
@@ -319,7 +332,7 @@ def main():
         "cpu_baseline": cpu,
         "stages_us": {"encode_query": round(encq_us, 3), "score_topk": round(topk_us, 3),
                       "gather_attend": round(gather_us, 3)},
-        "dense_baseline": dense, "parity_layer0": parity, "setup_s": round(t_setup, 1),
+        "dense_baseline": dense, "key_encode_bulk": key_encode, "parity_layer0": parity, "setup_s": round(t_setup, 1),
     }
     print(json.dumps(line, ensure_ascii=False))
 

@@ -16,6 +16,8 @@ struct hashattn_ctx {
     // TOPK scratch
     int32_t* blk_cum;
     int32_t blocks_pitch;
+    uint4* frags;                 // bf16 weight fragments of the matrix-core key encoder, per KV head
+    int64_t frag_bytes;
     // split partials shared by GATHER-ATT and the dense kernel
     float* part;
     int64_t part_floats;
@@ -210,13 +212,19 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
     if (splits > kMaxSplits) splits = kMaxSplits;
     ctx->part_floats = bh * splits * ha::kPartStride;
     const int64_t part_bytes = ctx->part_floats * (int64_t)sizeof(float);
-    ctx->scratch_bytes = hist_bytes + part_bytes;
+    ctx->frag_bytes = (int64_t)cfg->n_kv_heads * ha::encode_mfma_scratch_bytes_per_head();
+    ctx->scratch_bytes = hist_bytes + part_bytes + ctx->frag_bytes;
 
     if ((e = hipMalloc(reinterpret_cast<void**>(&ctx->blk_cum), hist_bytes)) != hipSuccess ||
-        (e = hipMalloc(reinterpret_cast<void**>(&ctx->part), part_bytes)) != hipSuccess) {
+        (e = hipMalloc(reinterpret_cast<void**>(&ctx->part), part_bytes)) != hipSuccess ||
+        (e = hipMalloc(reinterpret_cast<void**>(&ctx->frags), ctx->frag_bytes)) != hipSuccess) {
         const long long wanted = (long long)ctx->scratch_bytes;
         hashattn_destroy(ctx);
         return fail(nullptr, HASHATTN_HIP_ERROR, "create: allocating %lld scratch bytes: %s", wanted, hipGetErrorString(e));
+    }
+    if ((e = ha::setup_encode_mfma()) != hipSuccess) {
+        hashattn_destroy(ctx);
+        return fail(nullptr, HASHATTN_HIP_ERROR, "create: raising the LDS limit of the key encoder: %s", hipGetErrorString(e));
     }
     if ((e = ha::setup_score_topk(group)) != hipSuccess) {
         hashattn_destroy(ctx);
@@ -231,6 +239,7 @@ hashattn_status hashattn_destroy(hashattn_ctx* ctx)
     if (!ctx) return HASHATTN_OK;
     if (ctx->blk_cum) (void)hipFree(ctx->blk_cum);
     if (ctx->part) (void)hipFree(ctx->part);
+    if (ctx->frags) (void)hipFree(ctx->frags);
     delete ctx;
     return HASHATTN_OK;
 }
@@ -259,9 +268,10 @@ hashattn_status hashattn_encode_keys(hashattn_ctx* ctx, const hashattn_mlp* phi_
         if ((int64_t)cache->max_seq_len + n_new > ctx->cfg.max_context)
             return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "encode_keys: append would exceed max_context %lld", (long long)ctx->cfg.max_context);
     }
+    const ha::EncodeScratch enc{ctx->frags, ha::encode_mfma_scratch_bytes_per_head() / 16};
     const hipError_t e = ha::launch_encode_keys(view_of(phi_kv), view_of(ctx, cache), paged,
                                                 static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
-                                                batch, n_new, cache->max_seq_len, static_cast<hipStream_t>(stream));
+                                                batch, n_new, cache->max_seq_len, &enc, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(ctx, e, "encode_keys");
     if (k_new) cache->max_seq_len += (int32_t)n_new;
     return HASHATTN_OK;

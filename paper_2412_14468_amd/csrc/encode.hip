@@ -361,10 +361,12 @@ hipError_t launch_encode_query(const MlpView& phi, const uint16_t* q, int batch,
 
 hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
                               const uint16_t* k_new, const uint16_t* v_new,
-                              int batch, int64_t n_new, int max_seq_len, hipStream_t stream)
+                              int batch, int64_t n_new, int max_seq_len, const EncodeScratch* sc,
+                              hipStream_t stream)
 {
     const int H = kv.n_kv_heads;
     size_t lds_bytes = 0;
+    const bool mfma = sc && sc->frags && encode_mfma_supported(phi);    // bulk work goes to the matrix cores
     if (k_new) {
         if (n_new * batch <= 4 * kVecPerBlock) {
             // decode-time append: one GEMV-shaped launch writes rows and codes
@@ -377,19 +379,22 @@ hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
         } else {
             const dim3 cgrid((unsigned)((n_new * 16 + 255) / 256), H, batch);
             const dim3 egrid((unsigned)((n_new + kTile - 1) / kTile), H, batch);
-            if (hipError_t e = bulk_lds_setup(phi, paged, &lds_bytes); e != hipSuccess) return e;
-            if (paged) {
-                append_rows_kernel<true><<<cgrid, 256, 0, stream>>>(kv, k_new, v_new, n_new, max_seq_len);
-                encode_bulk_kernel<true><<<egrid, 256, lds_bytes, stream>>>(phi, kv, max_seq_len, n_new, 0);
+            if (paged) append_rows_kernel<true><<<cgrid, 256, 0, stream>>>(kv, k_new, v_new, n_new, max_seq_len);
+            else append_rows_kernel<false><<<cgrid, 256, 0, stream>>>(kv, k_new, v_new, n_new, max_seq_len);
+            if (mfma) {
+                if (hipError_t e = launch_encode_bulk_mfma(phi, kv, paged, batch, n_new, n_new, max_seq_len, 0, *sc, stream); e != hipSuccess) return e;
             } else {
-                append_rows_kernel<false><<<cgrid, 256, 0, stream>>>(kv, k_new, v_new, n_new, max_seq_len);
-                encode_bulk_kernel<false><<<egrid, 256, lds_bytes, stream>>>(phi, kv, max_seq_len, n_new, 0);
+                if (hipError_t e = bulk_lds_setup(phi, paged, &lds_bytes); e != hipSuccess) return e;
+                if (paged) encode_bulk_kernel<true><<<egrid, 256, lds_bytes, stream>>>(phi, kv, max_seq_len, n_new, 0);
+                else encode_bulk_kernel<false><<<egrid, 256, lds_bytes, stream>>>(phi, kv, max_seq_len, n_new, 0);
             }
         }
         bump_seq_lens_kernel<<<(batch + 255) / 256, 256, 0, stream>>>(kv.seq_lens, batch, (int)n_new);
     } else {
         const int64_t span = n_new < max_seq_len ? n_new : max_seq_len;
-        if (span > 0) {
+        if (span > 0 && mfma) {
+            if (hipError_t e = launch_encode_bulk_mfma(phi, kv, paged, batch, span, n_new, max_seq_len, 1, *sc, stream); e != hipSuccess) return e;
+        } else if (span > 0) {
             const dim3 egrid((unsigned)((span + kTile - 1) / kTile), H, batch);
             if (hipError_t e = bulk_lds_setup(phi, paged, &lds_bytes); e != hipSuccess) return e;
             if (paged)

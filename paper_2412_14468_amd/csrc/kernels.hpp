@@ -21,9 +21,24 @@ struct TopkScratch {
 hipError_t launch_encode_query(const MlpView& phi, const uint16_t* q, int batch, int n_heads,
                                uint32_t* q_codes, hipStream_t stream);
 
+// Scratch of the matrix-core bulk encoder: bf16 weight fragments of every KV head.
+struct EncodeScratch {
+    uint4* frags;
+    int64_t quads_per_head;        // 16-byte units per head
+};
+
+// sc == nullptr (or a network shape the matrix-core kernel does not cover): vector kernels only.
 hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
                               const uint16_t* k_new, const uint16_t* v_new,
-                              int batch, int64_t n_new, int max_seq_len, hipStream_t stream);
+                              int batch, int64_t n_new, int max_seq_len, const EncodeScratch* sc,
+                              hipStream_t stream);
+
+int64_t encode_mfma_scratch_bytes_per_head();
+bool encode_mfma_supported(const MlpView& phi);
+hipError_t setup_encode_mfma();
+hipError_t launch_encode_bulk_mfma(const MlpView& phi, const KvView& kv, bool paged, int batch, int64_t span,
+                                   int64_t n_new, int max_seq_len, int from_end, const EncodeScratch& sc,
+                                   hipStream_t stream);
 
 hipError_t setup_score_topk(int group);
 
