@@ -67,6 +67,14 @@ def lib():
                                                    C.c_void_p, C.c_void_p, C.c_int, C.c_int,
                                                    C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_double,
                                                    C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        L.ha_oracle_token_contributions.restype = None
+        L.ha_oracle_token_contributions.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int64,
+                                                    C.c_double, C.c_void_p]
+        L.ha_oracle_true_topk.restype = C.c_int64
+        L.ha_oracle_true_topk.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_int64, C.c_int64,
+                                          C.c_double, C.c_void_p]
+        L.ha_oracle_recall.restype = C.c_double
+        L.ha_oracle_recall.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64]
         _lib = L
     return _lib
 
@@ -246,6 +254,30 @@ def dense_attend(cache: Cache, b: int, h_kv: int, q_bf16: np.ndarray, n: int, sc
     lib().ha_oracle_dense_attend(C.byref(cache.c), b, h_kv, q.ctypes.data, n, float(scale),
                                  out.ctypes.data)
     return out
+
+
+# ------------------------------------------------------------------ quality of a SCORE function
+def token_contributions(cache: Cache, b: int, h_kv: int, q_bf16: np.ndarray, n: int, scale: float) -> np.ndarray:
+    """a_i * ||v_i||_2 of every token: its contribution to the dense output (section 4.2 lemma)."""
+    q = _chk(np.ascontiguousarray(q_bf16), np.uint16)
+    out = np.zeros(max(n, 1), dtype=np.float64)
+    lib().ha_oracle_token_contributions(C.byref(cache.c), b, h_kv, q.ctypes.data, n, float(scale), out.ctypes.data)
+    return out[:n]
+
+
+def true_topk(cache: Cache, b: int, h_kv: int, q_bf16: np.ndarray, n: int, k: int, scale: float) -> np.ndarray:
+    """I_true,k: the k tokens with the largest contribution, ascending."""
+    q = _chk(np.ascontiguousarray(q_bf16), np.uint16)
+    idx = np.zeros(max(min(k, n), 1), dtype=np.int32)
+    cnt = lib().ha_oracle_true_topk(C.byref(cache.c), b, h_kv, q.ctypes.data, n, k, float(scale), idx.ctypes.data)
+    return idx[:cnt].copy()
+
+
+def recall(chosen: np.ndarray, truth: np.ndarray) -> float:
+    """|chosen intersect truth| / |truth| (section 4)."""
+    a = _chk(np.ascontiguousarray(chosen), np.int32)
+    t = _chk(np.ascontiguousarray(truth), np.int32)
+    return float(lib().ha_oracle_recall(a.ctypes.data, a.shape[0], t.ctypes.data, t.shape[0]))
 
 
 # ------------------------------------------------------------------ whole step

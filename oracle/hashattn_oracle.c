@@ -11,6 +11,7 @@
  *              recent tokens always kept and the budget counting only retrieved tokens (section 5)
  *   - GATHER-ATT  softmax attention restricted to the index set (section 4)
  *   - SDPA     single-query dense attention (section 3.1)
+ *   - recall   of a selected set against the true pivotal tokens, ranked by a_i ||v_i|| (sections 4, 4.2)
  * All floating point is fp64.  No blocking, no fusion, no vectorisation.
  * It shares no code with the HIP library; only tests, the smoke check and the
  * benchmark's cpu_baseline leg may call it.  The product never does.
@@ -298,6 +299,75 @@ void ha_oracle_dense_attend(const ha_cache* c, int b, int h, const uint16_t* q_b
     for (int64_t i = 0; i < n; ++i) all[i] = (int32_t)i;
     ha_oracle_gather_attend(c, b, h, q_bf16, all, n, scale, out);
     free(all);
+}
+
+/* ------------------------------------------------ quality of a SCORE function (sections 4 and 4.2) */
+
+/* Contribution of every token of (b, h) to the dense attention output: a_i * ||v_i||_2, with a the
+ * softmax of scale <q, k_i> over all n tokens (the lemma on the best ordering for SDPA, section 4.2).
+ * contrib: n doubles. */
+void ha_oracle_token_contributions(const ha_cache* c, int b, int h, const uint16_t* q_bf16,
+                                   int64_t n, double scale, double* contrib)
+{
+    int d = c->head_dim;
+    if (n <= 0) return;
+    double m = -INFINITY;
+    for (int64_t i = 0; i < n; ++i) {
+        const uint16_t* kr = c->k + row_of(c, b, h, i) * d;
+        double s = 0.0;
+        for (int j = 0; j < d; ++j) s += bf16_to_double(q_bf16[j]) * bf16_to_double(kr[j]);
+        contrib[i] = s * scale;
+        if (contrib[i] > m) m = contrib[i];
+    }
+    double denom = 0.0;
+    for (int64_t i = 0; i < n; ++i) { contrib[i] = exp(contrib[i] - m); denom += contrib[i]; }
+    for (int64_t i = 0; i < n; ++i) {
+        const uint16_t* vr = c->v + row_of(c, b, h, i) * d;
+        double nv = 0.0;
+        for (int j = 0; j < d; ++j) nv += bf16_to_double(vr[j]) * bf16_to_double(vr[j]);
+        contrib[i] = contrib[i] / denom * sqrt(nv);
+    }
+}
+
+typedef struct { double key; int32_t id; } ha_dpair;
+
+static int cmp_key_desc_id_asc(const void* a, const void* b)
+{
+    const ha_dpair* x = (const ha_dpair*)a;
+    const ha_dpair* y = (const ha_dpair*)b;
+    if (x->key != y->key) return (x->key > y->key) ? -1 : 1;
+    return (x->id > y->id) - (x->id < y->id);
+}
+
+/* I_true,k: the min(k, n) tokens with the largest contribution (ties to the lower index), ascending.
+ * Returns the count. */
+int64_t ha_oracle_true_topk(const ha_cache* c, int b, int h, const uint16_t* q_bf16, int64_t n,
+                            int64_t k, double scale, int32_t* idx)
+{
+    int64_t ke = k < n ? k : n;
+    if (ke <= 0) return 0;
+    double* contrib = (double*)malloc(sizeof(double) * (size_t)n);
+    ha_oracle_token_contributions(c, b, h, q_bf16, n, scale, contrib);
+    ha_dpair* p = (ha_dpair*)malloc(sizeof(ha_dpair) * (size_t)n);
+    for (int64_t i = 0; i < n; ++i) { p[i].key = contrib[i]; p[i].id = (int32_t)i; }
+    qsort(p, (size_t)n, sizeof(ha_dpair), cmp_key_desc_id_asc);
+    for (int64_t i = 0; i < ke; ++i) idx[i] = p[i].id;
+    qsort(idx, (size_t)ke, sizeof(int32_t), cmp_i32);
+    free(p);
+    free(contrib);
+    return ke;
+}
+
+/* recall(I_n, I_true,k) = |I_n intersect I_true,k| / |I_true,k| (section 4); both lists hold distinct
+ * token ids in any order.  An empty I_true gives 1. */
+double ha_oracle_recall(const int32_t* chosen, int64_t n_chosen, const int32_t* truth, int64_t n_truth)
+{
+    if (n_truth <= 0) return 1.0;
+    int64_t hit = 0;
+    for (int64_t i = 0; i < n_truth; ++i)
+        for (int64_t j = 0; j < n_chosen; ++j)
+            if (chosen[j] == truth[i]) { ++hit; break; }
+    return (double)hit / (double)n_truth;
 }
 
 /* ------------------------------------------------ one decode layer-step */

@@ -148,6 +148,15 @@ def mapping_weights(rng, n_heads: int, dims) -> List[np.ndarray]:
     return out
 
 
+def shared_projection_weights(rng, n_q_heads: int, n_kv_heads: int, d: int = 128, bits: int = 32):
+    """One-layer mappings that share a Gaussian projection between a KV head and the query heads of its
+    group: sign random projections, the locality-sensitive hash of the angle (used by the recall
+    harness as a mapping whose quality is known without training).  Returns (w_q, w_kv)."""
+    w_kv = rng.standard_normal((n_kv_heads, d, bits)).astype(np.float32)
+    w_q = np.repeat(w_kv, n_q_heads // n_kv_heads, axis=0)
+    return [np.ascontiguousarray(w_q)], [w_kv]
+
+
 def draw_lengths(rng, batch: int, lo: int, hi: int) -> np.ndarray:
     """Context lengths log-uniform in [lo, hi]."""
     u = rng.uniform(math.log(lo), math.log(hi), size=batch)
