@@ -75,6 +75,20 @@ def lib():
                                           C.c_double, C.c_void_p]
         L.ha_oracle_recall.restype = C.c_double
         L.ha_oracle_recall.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.c_int64]
+        L.ha_oracle_encode_vec_wide.restype = None
+        L.ha_oracle_encode_vec_wide.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        L.ha_oracle_score_wide.restype = C.c_int32
+        L.ha_oracle_score_wide.argtypes = [C.c_void_p, C.c_void_p, C.c_int]
+        L.ha_oracle_encode_query_wide.restype = None
+        L.ha_oracle_encode_query_wide.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        L.ha_oracle_encode_keys_wide.restype = None
+        L.ha_oracle_encode_keys_wide.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p,
+                                                 C.c_int, C.c_int64, C.c_void_p]
+        L.ha_oracle_decode_step_wide.restype = None
+        L.ha_oracle_decode_step_wide.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int,
+                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_int,
+                                                 C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_double,
+                                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         _lib = L
     return _lib
 
@@ -114,7 +128,7 @@ class Mlp:
                 assert w.shape[1] == self.weights[l - 1].shape[2]
             s.W[l] = w.ctypes.data
             s.bias[l] = _ptr(self.biases[l])
-        assert s.dims[s.n_layers] == 32
+        assert s.dims[s.n_layers] % 32 == 0 and 32 <= s.dims[s.n_layers] <= 512
         self.c = s
 
     @property
@@ -321,4 +335,76 @@ def decode_step(phi_q: Optional[Mlp], phi_kv: Optional[Mlp], cache: Cache, q_bf1
                                 C.addressof(cache.c), q.ctypes.data, _ptr(k_new), _ptr(v_new),
                                 B, Hq, kps.ctypes.data, k_max, float(scale), qc.ctypes.data,
                                 idx.ctypes.data, count.ctypes.data, thr.ctypes.data, out.ctypes.data)
+    return dict(q_codes=qc, idx=idx, count=count, threshold=thr, out=out)
+
+
+# ------------------------------------------------------------------ wider signatures (words x 32 bits)
+def encode_vec_wide(mlp: Mlp, head: int, x_bf16: np.ndarray, words: int):
+    """Code words [words] and pre-sign activations [32 words] of one vector."""
+    x = _chk(np.ascontiguousarray(x_bf16), np.uint16)
+    code = np.zeros(words, dtype=np.uint32)
+    act = np.zeros(32 * words, dtype=np.float64)
+    lib().ha_oracle_encode_vec_wide(C.byref(mlp.c), head, x.ctypes.data, words, code.ctypes.data, act.ctypes.data)
+    return code, act
+
+
+def score_wide(q_code: np.ndarray, k_code: np.ndarray) -> int:
+    q = _chk(np.ascontiguousarray(q_code), np.uint32)
+    k = _chk(np.ascontiguousarray(k_code), np.uint32)
+    assert q.shape == k.shape and q.ndim == 1
+    return int(lib().ha_oracle_score_wide(q.ctypes.data, k.ctypes.data, q.shape[0]))
+
+
+def scores_wide(q_code: np.ndarray, k_codes: np.ndarray) -> np.ndarray:
+    """k_codes [n, words] -> similarities [n]."""
+    return np.array([score_wide(q_code, kc) for kc in k_codes], dtype=np.int32)
+
+
+def encode_query_wide(phi_q: Mlp, q_bf16: np.ndarray, words: int):
+    q = _chk(np.ascontiguousarray(q_bf16), np.uint16)
+    B, H, d = q.shape
+    codes = np.zeros((B, H, words), dtype=np.uint32)
+    act = np.zeros((B, H, 32 * words), dtype=np.float64)
+    lib().ha_oracle_encode_query_wide(C.byref(phi_q.c), q.ctypes.data, B, d, words, codes.ctypes.data, act.ctypes.data)
+    return codes, act
+
+
+def encode_keys_wide(phi_kv: Mlp, cache: Cache, codes: np.ndarray, k_new, v_new, n_new: int, want_act: bool = False):
+    """codes: uint32 array shaped like the key cache without d plus a trailing axis of words (updated in place)."""
+    codes = _chk(codes, np.uint32)
+    words = codes.shape[-1]
+    act = None
+    if want_act:
+        act = np.zeros((cache.batch, cache.c.n_kv_heads, n_new, 32 * words), dtype=np.float64)
+    if k_new is not None:
+        k_new = _chk(np.ascontiguousarray(k_new), np.uint16)
+        v_new = _chk(np.ascontiguousarray(v_new), np.uint16)
+    lib().ha_oracle_encode_keys_wide(C.byref(phi_kv.c), C.byref(cache.c), codes.ctypes.data, words, _ptr(k_new),
+                                     _ptr(v_new), cache.batch, n_new, _ptr(act))
+    return act
+
+
+def decode_step_wide(phi_q: Optional[Mlp], phi_kv: Optional[Mlp], cache: Cache, codes: np.ndarray, q_bf16: np.ndarray,
+                     k_per_seq: np.ndarray, scale: float, k_new=None, v_new=None, q_codes=None,
+                     n_sink: int = 0, n_local: int = 0):
+    """decode_step with codes of words x 32 bits (codes: trailing axis words; q_codes [B,Hq,words])."""
+    codes = _chk(codes, np.uint32)
+    words = codes.shape[-1]
+    q = _chk(np.ascontiguousarray(q_bf16), np.uint16)
+    B, Hq, d = q.shape
+    kps = _chk(np.ascontiguousarray(k_per_seq), np.int32)
+    k_max = int(kps.max())
+    qc = np.zeros((B, Hq, words), dtype=np.uint32) if phi_q is not None else _chk(np.ascontiguousarray(q_codes).copy(), np.uint32)
+    if k_new is not None:
+        k_new = _chk(np.ascontiguousarray(k_new), np.uint16)
+        v_new = _chk(np.ascontiguousarray(v_new), np.uint16)
+    idx = np.full((B, Hq, k_max + n_sink + n_local), -1, dtype=np.int32)
+    count = np.zeros((B, Hq), dtype=np.int32)
+    thr = np.zeros((B, Hq), dtype=np.int32)
+    out = np.zeros((B, Hq, d), dtype=np.float64)
+    lib().ha_oracle_decode_step_wide(None if phi_q is None else C.addressof(phi_q.c),
+                                     None if phi_kv is None else C.addressof(phi_kv.c),
+                                     C.addressof(cache.c), codes.ctypes.data, words, q.ctypes.data, _ptr(k_new), _ptr(v_new),
+                                     B, Hq, kps.ctypes.data, k_max, n_sink, n_local, float(scale), qc.ctypes.data,
+                                     idx.ctypes.data, count.ctypes.data, thr.ctypes.data, out.ctypes.data)
     return dict(q_codes=qc, idx=idx, count=count, threshold=thr, out=out)

@@ -434,3 +434,115 @@ void ha_oracle_decode_step_window(const ha_mlp* phi_q, const ha_mlp* phi_kv, ha_
         free(scores);
     }
 }
+
+/* ------------------------------------------------ wider signatures (section 5.3 ablation on bit width;
+ * the SCORE latency table of the appendix lists 64 to 512 bits)
+ *
+ * A code of b = 32 * words bits is `words` consecutive uint32; output unit j of F goes to bit j % 32
+ * of word j / 32.  The similarity is b - bitcount(xor) summed over the words, an integer in 0..b.
+ * Code stores have the layout of the key cache without the d axis and with a trailing axis of
+ * `words`; they are passed separately from the ha_cache (whose `codes` member is not used here). */
+
+void ha_oracle_encode_vec_wide(const ha_mlp* m, int head, const uint16_t* x_bf16, int words,
+                               uint32_t* code, double* act)
+{
+    double cur[512], nxt[512];
+    int n_in = m->dims[0];
+    for (int i = 0; i < n_in; ++i) cur[i] = bf16_to_double(x_bf16[i]);
+    for (int l = 0; l < m->n_layers; ++l) {
+        int di = m->dims[l], dout = m->dims[l + 1];
+        const float* W = m->W[l] + (int64_t)head * di * dout;
+        for (int j = 0; j < dout; ++j) {
+            double z = 0.0;
+            for (int i = 0; i < di; ++i) z += cur[i] * (double)W[(int64_t)i * dout + j];
+            if (m->bias[l]) z += (double)m->bias[l][(int64_t)head * dout + j];
+            if (l + 1 < m->n_layers) z = z / (1.0 + exp(-z));
+            nxt[j] = z;
+        }
+        memcpy(cur, nxt, sizeof(double) * dout);
+    }
+    for (int w = 0; w < words; ++w) code[w] = 0;
+    for (int j = 0; j < HA_BITS * words; ++j) {
+        if (act) act[j] = cur[j];
+        if (cur[j] > 0.0) code[j / 32] |= (uint32_t)1 << (j % 32);
+    }
+}
+
+int32_t ha_oracle_score_wide(const uint32_t* q_code, const uint32_t* k_code, int words)
+{
+    int32_t h = 0;
+    for (int w = 0; w < words; ++w) {
+        uint32_t x = q_code[w] ^ k_code[w];
+        while (x) { h += (int32_t)(x & 1u); x >>= 1; }
+    }
+    return HA_BITS * words - h;
+}
+
+/* q [B][Hq][d] -> q_codes [B][Hq][words], act [B][Hq][32 words] (optional) */
+void ha_oracle_encode_query_wide(const ha_mlp* phi_q, const uint16_t* q, int batch, int d, int words,
+                                 uint32_t* q_codes, double* act)
+{
+    int H = phi_q->n_heads;
+    for (int b = 0; b < batch; ++b)
+        for (int h = 0; h < H; ++h) {
+            int64_t o = (int64_t)b * H + h;
+            ha_oracle_encode_vec_wide(phi_q, h, q + o * d, words, q_codes + o * words,
+                                      act ? act + o * HA_BITS * words : NULL);
+        }
+}
+
+/* as ha_oracle_encode_keys, codes [rows][words] */
+void ha_oracle_encode_keys_wide(const ha_mlp* phi_kv, ha_cache* c, uint32_t* codes, int words,
+                                const uint16_t* k_new, const uint16_t* v_new, int batch, int64_t n_new, double* act)
+{
+    int H = c->n_kv_heads, d = c->head_dim;
+    for (int b = 0; b < batch; ++b) {
+        int64_t len = c->seq_lens[b];
+        int64_t start = k_new ? len : (len > n_new ? len - n_new : 0);
+        int64_t cnt = k_new ? n_new : len - start;
+#pragma omp parallel for schedule(static)
+        for (int64_t j = 0; j < cnt; ++j) {
+            for (int h = 0; h < H; ++h) {
+                int64_t r = row_of(c, b, h, start + j);
+                if (k_new) {
+                    int64_t s = (((int64_t)b * H + h) * n_new + j) * d;
+                    memcpy(c->k + r * d, k_new + s, sizeof(uint16_t) * d);
+                    memcpy(c->v + r * d, v_new + s, sizeof(uint16_t) * d);
+                }
+                double* a = act ? act + (((int64_t)b * H + h) * n_new + j) * HA_BITS * words : NULL;
+                ha_oracle_encode_vec_wide(phi_kv, h, c->k + r * d, words, codes + r * words, a);
+            }
+        }
+        if (k_new) c->seq_lens[b] = (int32_t)(len + n_new);
+    }
+}
+
+/* The decode step with wide codes and the always-kept window (n_sink = n_local = 0: none).
+ * q_codes [B][Hq][words]; idx rows of k_max + n_sink + n_local entries. */
+void ha_oracle_decode_step_wide(const ha_mlp* phi_q, const ha_mlp* phi_kv, ha_cache* c, uint32_t* codes, int words,
+                                const uint16_t* q, const uint16_t* k_new, const uint16_t* v_new,
+                                int batch, int n_q_heads, const int32_t* k_per_seq, int64_t k_max,
+                                int64_t n_sink, int64_t n_local,
+                                double scale, uint32_t* q_codes, int32_t* idx, int32_t* count,
+                                int32_t* threshold, double* out)
+{
+    int d = c->head_dim, Hq = n_q_heads, g = Hq / c->n_kv_heads;
+    int64_t pitch = k_max + n_sink + n_local;
+    if (k_new) ha_oracle_encode_keys_wide(phi_kv, c, codes, words, k_new, v_new, batch, 1, NULL);
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t bh = 0; bh < (int64_t)batch * Hq; ++bh) {
+        int b = (int)(bh / Hq), h = (int)(bh % Hq), hk = h / g;
+        int64_t n = c->seq_lens[b];
+        const uint16_t* qv = q + bh * d;
+        if (phi_q) ha_oracle_encode_vec_wide(phi_q, h, qv, words, q_codes + bh * words, NULL);   /* else: given */
+        int32_t* scores = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+        for (int64_t t = 0; t < n; ++t)
+            scores[t] = ha_oracle_score_wide(q_codes + bh * words, codes + row_of(c, b, hk, t) * words, words);
+        int32_t T = 0;
+        int64_t cnt = ha_oracle_topk_window(scores, n, k_per_seq[b], n_sink, n_local, idx + bh * pitch, &T, NULL);
+        count[bh] = (int32_t)cnt;
+        threshold[bh] = T;
+        ha_oracle_gather_attend(c, b, hk, qv, idx + bh * pitch, cnt, scale, out + bh * d);
+        free(scores);
+    }
+}
