@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--score-table", action="store_true",
+                    help="also time SCORE + TOPK alone on uniform random codes of 32..512 bits at this workload's shape")
     ap.add_argument("--sink", type=int, default=0, help="always keep this many first tokens (k counts the rest)")
     ap.add_argument("--local", type=int, default=0, help="always keep this many most recent tokens")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -266,6 +268,33 @@ def main():
                   "key_read_GBps": round(n_vec * d * 2 / (enc_us * 1e-6) / 1e9, 1),
                   "note": "fp32-equivalent flops of the mapping; run as 2-3 bf16 MFMA passes per layer"}
 
+    # ---- SCORE + TOPK alone for signatures of 32..512 bits (the paper's SCORE latency table lists 64..512)
+    score_table = None
+    if args.score_table:
+        score_table = {}
+        gen = torch.Generator(device="cuda:0")
+        gen.manual_seed(W.BASE_SEED + 512)
+        s0 = layers[0]
+        for bits in (32, 64, 128, 256, 512):
+            words = bits // 32
+            wctx = ctx if bits == 32 else ha.Context(Hq, Hkv, B, n_cap, k_max, page_size=cfg.page_size, bits=bits)
+            n_ring = max(2, min(ring, (1 << 30) // max(1, s0.codes.numel() * 4 * words)))
+            shape = tuple(s0.codes.shape) + ((words,) if words > 1 else ())
+            rings = [(torch.randint(-2 ** 31, 2 ** 31 - 1, shape, dtype=torch.int32, device="cuda:0", generator=gen),
+                      torch.randint(-2 ** 31, 2 ** 31 - 1, (B, Hq) + ((words,) if words > 1 else ()), dtype=torch.int32,
+                                    device="cuda:0", generator=gen)) for _ in range(n_ring)]
+            caches = [ha.KvCache(s0.k, s0.v, cds, s0.seq_lens, s0.cache.max_seq_len, page_table=s0.page_table) for cds, _ in rings]
+
+            def wide_sweep():
+                for cache_w, (_, qcw) in zip(caches, rings):
+                    wctx.hashattn_score_topk(qcw, cache_w, B, s0.k_per_seq, s0.k_max, s0.idx, s0.count, s0.threshold)
+            rp = capture(torch, wide_sweep) if not args.no_graph else wide_sweep
+            rp()
+            us = event_time_us(torch, rp, 10) / n_ring
+            code_bytes = sum(int(n) for n in s0.lens_host) * Hkv * 4 * words
+            score_table[str(bits)] = {"us": round(us, 2), "code_GBps": round(code_bytes / (us * 1e-6) / 1e9, 1)}
+            del rings, caches
+
     # ---- in-house dense decode on the same ring
     dense = None
     if not args.no_dense:
@@ -332,7 +361,7 @@ def main():
         "cpu_baseline": cpu,
         "stages_us": {"encode_query": round(encq_us, 3), "score_topk": round(topk_us, 3),
                       "gather_attend": round(gather_us, 3)},
-        "dense_baseline": dense, "key_encode_bulk": key_encode, "parity_layer0": parity, "setup_s": round(t_setup, 1),
+        "dense_baseline": dense, "key_encode_bulk": key_encode, "score_topk_by_bits": score_table, "parity_layer0": parity, "setup_s": round(t_setup, 1),
     }
     print(json.dumps(line, ensure_ascii=False))
 

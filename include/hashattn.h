@@ -21,7 +21,8 @@
  *     hashattn_last_error() gives a readable message for the last failure on
  *     that context (or of hashattn_create when ctx == NULL).
  *   - bf16 tensors are 16-bit brain floats; head_dim is 128; codes have 32
- *     bits.  Query head h uses KV head h / (n_q_heads / n_kv_heads).
+ *     bits unless the context is created for wider signatures (below).  Query
+ *     head h uses KV head h / (n_q_heads / n_kv_heads).
  *   - Bit order of a code: output unit j of the mapping network is bit j
  *     (least significant bit = unit 0); bit = 1 iff the activation is > 0
  *     (phi(x) = relu(sign(F(x))), section 4.1, eq. 2; sign(0) gives 0).
@@ -29,6 +30,15 @@
  *       contiguous:  (b * n_kv_heads + h) * n_max + t
  *       paged:       (page_table[b][t / page_size] * n_kv_heads + h) * page_size + t % page_size
  *     in k, v (rows of head_dim bf16) and in codes (one uint32 per row).
+ *   - Wider signatures (the paper's ablation on the number of bits; its SCORE
+ *     latency table lists 64 to 512 bits): with bits = b = 32 W in the config,
+ *     a code is W consecutive uint32 (codes hold W words per row, q_codes
+ *     [batch][n_q_heads][W]); output unit j of the mapping is bit j % 32 of
+ *     word j / 32; the score of a token is b - bitcount(xor), 0..b; the
+ *     mapping networks end in b outputs.  hashattn_encode_* produce up to 256
+ *     bits (512-bit codes must be supplied by the caller); `threshold` is
+ *     stored as min(T, 255); max_context is at most 2 Mi tokens.  Everything
+ *     else reads as for 32 bits.
  */
 #ifndef HASHATTN_H
 #define HASHATTN_H
@@ -55,7 +65,7 @@ typedef struct {
     int32_t head_dim;      /* must be 128 */
     int32_t n_q_heads;     /* multiple of n_kv_heads; group size 1, 2, 4 or 8 */
     int32_t n_kv_heads;
-    int32_t bits;          /* must be 32 */
+    int32_t bits;          /* signature width b: 32, 64, 128, 256 or 512 (see "Wider signatures") */
     int32_t page_size;     /* 0 = contiguous KV cache, 16 = paged */
     int32_t max_batch;
     int64_t max_context;   /* largest sequence length any call will see */

@@ -79,6 +79,8 @@ def lib():
         L.ha_oracle_encode_vec_wide.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.ha_oracle_score_wide.restype = C.c_int32
         L.ha_oracle_score_wide.argtypes = [C.c_void_p, C.c_void_p, C.c_int]
+        L.ha_oracle_scores_wide.restype = None
+        L.ha_oracle_scores_wide.argtypes = [C.c_void_p, C.c_void_p, C.c_int64, C.c_int, C.c_void_p]
         L.ha_oracle_encode_query_wide.restype = None
         L.ha_oracle_encode_query_wide.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
         L.ha_oracle_encode_keys_wide.restype = None
@@ -357,7 +359,12 @@ def score_wide(q_code: np.ndarray, k_code: np.ndarray) -> int:
 
 def scores_wide(q_code: np.ndarray, k_codes: np.ndarray) -> np.ndarray:
     """k_codes [n, words] -> similarities [n]."""
-    return np.array([score_wide(q_code, kc) for kc in k_codes], dtype=np.int32)
+    q = _chk(np.ascontiguousarray(q_code), np.uint32)
+    k = _chk(np.ascontiguousarray(k_codes), np.uint32)
+    assert k.ndim == 2 and k.shape[1] == q.shape[0]
+    out = np.zeros(k.shape[0], dtype=np.int32)
+    lib().ha_oracle_scores_wide(q.ctypes.data, k.ctypes.data, k.shape[0], q.shape[0], out.ctypes.data)
+    return out
 
 
 def encode_query_wide(phi_q: Mlp, q_bf16: np.ndarray, words: int):

@@ -478,6 +478,11 @@ int32_t ha_oracle_score_wide(const uint32_t* q_code, const uint32_t* k_code, int
     return HA_BITS * words - h;
 }
 
+void ha_oracle_scores_wide(const uint32_t* q_code, const uint32_t* k_codes, int64_t n, int words, int32_t* scores)
+{
+    for (int64_t i = 0; i < n; ++i) scores[i] = ha_oracle_score_wide(q_code, k_codes + i * words, words);
+}
+
 /* q [B][Hq][d] -> q_codes [B][Hq][words], act [B][Hq][32 words] (optional) */
 void ha_oracle_encode_query_wide(const ha_mlp* phi_q, const uint16_t* q, int batch, int d, int words,
                                  uint32_t* q_codes, double* act)

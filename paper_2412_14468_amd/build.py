@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libhashattn.so")
-SOURCES = ["api.hip", "encode.hip", "encode_mfma.hip", "score_topk.hip", "attend.hip"]
+SOURCES = ["api.hip", "encode.hip", "encode_mfma.hip", "score_topk.hip", "score_topk_wide.hip", "attend.hip"]
 HEADERS = ["common.hpp", "kernels.hpp"]
 
 

@@ -54,8 +54,10 @@ hashattn_status check_mlp(hashattn_ctx* ctx, const hashattn_mlp* m, int n_heads,
         return fail(ctx, HASHATTN_INVALID_ARG, "%s: network has %d heads, expected %d", what, m->n_heads, n_heads);
     if (m->n_layers < 1 || m->n_layers > 3)
         return fail(ctx, HASHATTN_UNSUPPORTED, "%s: n_layers %d not in 1..3", what, m->n_layers);
-    if (m->dims[0] != ha::kHeadDim || m->dims[m->n_layers] != ha::kBits)
-        return fail(ctx, HASHATTN_UNSUPPORTED, "%s: network must map 128 inputs to 32 outputs", what);
+    if (m->dims[0] != ha::kHeadDim || m->dims[m->n_layers] != ctx->cfg.bits)
+        return fail(ctx, HASHATTN_UNSUPPORTED, "%s: network must map 128 inputs to %d outputs (the context's bits)", what, ctx->cfg.bits);
+    if (ctx->cfg.bits > 256)
+        return fail(ctx, HASHATTN_UNSUPPORTED, "%s: the mapping kernels produce at most 256 bits (SCORE/TOPK take up to 512)", what);
     for (int l = 1; l < m->n_layers; ++l)
         if (!pow2_width(m->dims[l]))
             return fail(ctx, HASHATTN_UNSUPPORTED, "%s: hidden width %d not in {32,64,128,256}", what, m->dims[l]);
@@ -127,13 +129,13 @@ ha::KvView view_of(const hashattn_ctx* ctx, const hashattn_kv* kv)
 int pick_unit_tokens(const hashattn_ctx* ctx, int batch, int max_seq_len, bool mixed)
 {
     const int64_t lanes = (int64_t)batch * ctx->cfg.n_kv_heads;
-    const int cap = mixed ? kMaxUnit / 2 : kMaxUnit;
+    const int cap = (mixed || ctx->cfg.bits > 32) ? kMaxUnit / 2 : kMaxUnit;      // wide codes: units of at most 1024
     int unit = kMinUnit;
     auto blocks = [&](int u) { return (max_seq_len + (int64_t)u * ha::kTopkWavesPerBlock - 1) / ((int64_t)u * ha::kTopkWavesPerBlock); };
     // a 16-wave block fills a CU: prefer one round of blocks over the 256 CUs
     while (unit < cap && lanes * blocks(unit) > 256) unit *= 2;
     // never more blocks per sequence than the scratch pitch
-    while (unit < kMaxUnit && blocks(unit) > ctx->blocks_pitch) unit *= 2;
+    while (unit < (ctx->cfg.bits > 32 ? kMaxUnit / 2 : kMaxUnit) && blocks(unit) > ctx->blocks_pitch) unit *= 2;
     return unit;
 }
 
@@ -175,7 +177,8 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
     if (!out || !cfg) return fail(nullptr, HASHATTN_INVALID_ARG, "create: NULL argument");
     *out = nullptr;
     if (cfg->head_dim != ha::kHeadDim) return fail(nullptr, HASHATTN_UNSUPPORTED, "create: head_dim %d, only 128 is supported", cfg->head_dim);
-    if (cfg->bits != ha::kBits) return fail(nullptr, HASHATTN_UNSUPPORTED, "create: bits %d, only 32 is supported", cfg->bits);
+    if (cfg->bits != 32 && cfg->bits != 64 && cfg->bits != 128 && cfg->bits != 256 && cfg->bits != 512)
+        return fail(nullptr, HASHATTN_UNSUPPORTED, "create: bits %d not in {32,64,128,256,512}", cfg->bits);
     if (cfg->n_kv_heads < 1 || cfg->n_q_heads < 1 || cfg->n_q_heads % cfg->n_kv_heads)
         return fail(nullptr, HASHATTN_INVALID_ARG, "create: n_q_heads %d must be a positive multiple of n_kv_heads %d", cfg->n_q_heads, cfg->n_kv_heads);
     const int group = cfg->n_q_heads / cfg->n_kv_heads;
@@ -184,7 +187,8 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
     if (cfg->page_size != 0 && cfg->page_size != ha::kPage)
         return fail(nullptr, HASHATTN_UNSUPPORTED, "create: page_size %d, only 0 (contiguous) or 16", cfg->page_size);
     if (cfg->max_batch < 1 || cfg->max_batch > 65535) return fail(nullptr, HASHATTN_INVALID_ARG, "create: max_batch %d not in 1..65535", cfg->max_batch);
-    const int64_t context_limit = (int64_t)ha::kMaxTopkBlocks * ha::kTopkWavesPerBlock * kMaxUnit;   // 4 Mi tokens
+    const int64_t context_limit = (int64_t)ha::kMaxTopkBlocks * ha::kTopkWavesPerBlock *
+                                  (cfg->bits > 32 ? kMaxUnit / 2 : kMaxUnit);       // 4 Mi tokens (2 Mi with wide codes)
     if (cfg->max_context < 1 || cfg->max_context > context_limit)
         return fail(nullptr, HASHATTN_INVALID_ARG, "create: max_context %lld not in 1..%lld", (long long)cfg->max_context,
                     (long long)context_limit);
@@ -205,7 +209,7 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
     int64_t pitch = (cfg->max_context + (int64_t)kMinUnit * ha::kTopkWavesPerBlock - 1) / ((int64_t)kMinUnit * ha::kTopkWavesPerBlock);
     if (pitch > ha::kMaxTopkBlocks) pitch = ha::kMaxTopkBlocks;
     ctx->blocks_pitch = (int32_t)pitch;
-    const int64_t hist_bytes = bh * pitch * ha::kCumRow * (int64_t)sizeof(int32_t);
+    const int64_t hist_bytes = bh * pitch * (cfg->bits + 2) * (int64_t)sizeof(int32_t);   // rows C(0..bits) and a zero
     int64_t splits = (cfg->max_context + 63) / 64;               // dense needs more splits than gather
     int64_t want = 8192 / bh; if (want < 16) want = 16;
     if (splits > want) splits = want;
@@ -310,8 +314,11 @@ hashattn_status hashattn_score_topk_window(hashattn_ctx* ctx, const uint32_t* q_
     const int unit = pick_unit_tokens(ctx, batch, cache->max_seq_len, k_per_seq != nullptr);
     const ha::TopkCall call{q_codes, k_per_seq, k_max, n_sink, n_local, batch, ctx->cfg.n_q_heads, cache->max_seq_len,
                             idx, count, threshold};
-    const hipError_t e = ha::launch_score_topk(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group, call, unit, sc,
-                                               static_cast<hipStream_t>(stream));
+    const hipError_t e = ctx->cfg.bits == ha::kBits
+        ? ha::launch_score_topk(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group, call, unit, sc,
+                                static_cast<hipStream_t>(stream))
+        : ha::launch_score_topk_wide(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group, ctx->cfg.bits / ha::kBits,
+                                     call, unit, sc, static_cast<hipStream_t>(stream));
     return e == hipSuccess ? HASHATTN_OK : hip_fail(ctx, e, "score_topk");
 }
 

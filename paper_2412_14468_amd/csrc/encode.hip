@@ -89,21 +89,29 @@ template <int MODE, bool PAGED>
 __device__ __forceinline__ void store_codes(const float (*a)[kMaxWidth], int n_heads, int head, int v0,
                                             const uint16_t* __restrict__ x, const uint16_t* __restrict__ v_new,
                                             int n_vec, int n_new, uint32_t* __restrict__ q_codes,
-                                            const KvView& c, int n_cap)
+                                            const KvView& c, int n_cap, int words = 1)
 {
-    // thread (v = tid / 32, j = tid % 32) owns bit j of vector v; a wave ballot packs two vectors
+    // thread (v = tid / 32, j = tid % 32) owns bit j of every code word of vector v (unit 32 w + j of
+    // word w); a wave ballot packs one word of two vectors
     const int tid = threadIdx.x;
     const int v = tid >> 5, j = tid & 31, vec = v0 + v;
-    const uint64_t mask = __ballot(a[v][j] > 0.f);
-    const uint32_t code = (uint32_t)((tid & 32) ? (mask >> 32) : mask);
-    if (vec < n_vec) {
-        const int b = MODE == 0 ? vec : vec / n_new, jn = MODE == 0 ? 0 : vec - b * n_new;
-        if constexpr (MODE == 0) {
-            if (j == 0) q_codes[(int64_t)b * n_heads + head] = code;
-        } else {
-            const int64_t row = row_of<PAGED>(c, b, head, min(c.seq_lens[b], n_cap) + jn);
+    const bool live = vec < n_vec;
+    const int b = MODE == 0 ? vec : vec / n_new, jn = MODE == 0 ? 0 : vec - b * n_new;
+    int64_t row = 0;
+    if constexpr (MODE == 1) {
+        if (live) row = row_of<PAGED>(c, b, head, min(c.seq_lens[b], n_cap) + jn);
+    }
+    for (int w = 0; w < words; ++w) {
+        const uint64_t mask = __ballot(a[v][32 * w + j] > 0.f);
+        const uint32_t code = (uint32_t)((tid & 32) ? (mask >> 32) : mask);
+        if (live && j == 0) {
+            if constexpr (MODE == 0) q_codes[((int64_t)b * n_heads + head) * words + w] = code;
+            else c.codes[row * words + w] = code;
+        }
+    }
+    if (live) {
+        if constexpr (MODE == 1) {
             const int64_t src = ((int64_t)b * n_heads + head) * n_new + jn;
-            if (j == 0) c.codes[row] = code;
             // 32 threads copy the 256-byte K row and V row, 16 bytes each (16 + 16 threads)
             const uint4* from = reinterpret_cast<const uint4*>((j < 16 ? x : v_new) + src * kHeadDim) + (j & 15);
             uint4* to = reinterpret_cast<uint4*>(const_cast<uint16_t*>(j < 16 ? c.k : c.v) + row * kHeadDim) + (j & 15);
@@ -124,7 +132,8 @@ __global__ __launch_bounds__(256) void encode_vec_kernel(MlpView phi, int n_head
     load_vectors<MODE>(act[0], n_heads, head, v0, x, n_vec, n_new);
     __syncthreads();
     const int cur = mlp_gemv(phi, head, act, red);
-    store_codes<MODE, PAGED>(act[cur], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+    store_codes<MODE, PAGED>(act[cur], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap,
+                             phi.dims[phi.n_layers] / kBits);
 }
 
 // ---- shapes known at compile time: every thread fetches all its weights of all layers up front,
@@ -202,7 +211,9 @@ void launch_encode_vec(const MlpView& phi, dim3 grid, int n_heads, const uint16_
                        int n_vec, int n_new, uint32_t* q_codes, const KvView& c, int n_cap, hipStream_t stream)
 {
     const int nl = phi.n_layers, d1 = phi.dims[1], d2 = phi.dims[2];
-    if (nl == 1)
+    if (phi.dims[nl] != kBits)           // wider signatures: the general kernel
+        encode_vec_kernel<MODE, PAGED><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+    else if (nl == 1)
         encode_vec_fixed_kernel<MODE, PAGED, 1, 32, 32><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
     else if (nl == 2 && d1 == 128)
         encode_vec_fixed_kernel<MODE, PAGED, 2, 128, 32><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
@@ -311,11 +322,13 @@ __global__ __launch_bounds__(256) void encode_bulk_kernel(MlpView phi, KvView c,
         __syncthreads();
         float* t = in; in = out; out = t;
     }
-    if (tid < n_tok) {
+    const int words = phi.dims[phi.n_layers] / kBits;          // unit 32 w + j -> bit j of word w
+    for (int o = tid; o < n_tok * words; o += 256) {
+        const int t = o / words, w = o - t * words;
         uint32_t code = 0u;
 #pragma unroll
-        for (int j = 0; j < kBits; ++j) code |= (in[tid * P + j] > 0.f ? 1u : 0u) << j;
-        c.codes[row_of<PAGED>(c, b, head, (int)(start + t0 + tid))] = code;
+        for (int j = 0; j < kBits; ++j) code |= (in[t * P + 32 * w + j] > 0.f ? 1u : 0u) << j;
+        c.codes[row_of<PAGED>(c, b, head, (int)(start + t0 + t)) * words + w] = code;
     }
 }
 

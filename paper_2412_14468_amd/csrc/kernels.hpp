@@ -58,6 +58,11 @@ struct TopkCall {
 hipError_t launch_score_topk(const KvView& kv, bool paged, int group, const TopkCall& call, int unit_tokens,
                              const TopkScratch& sc, hipStream_t stream);
 
+// Signatures of 32 * words bits (words = 2, 4, 8, 16): codes and q_codes carry a trailing axis of
+// `words`, blk_cum rows have 32 * words + 2 ints, unit_tokens is at most 1024.
+hipError_t launch_score_topk_wide(const KvView& kv, bool paged, int group, int words, const TopkCall& call,
+                                  int unit_tokens, const TopkScratch& sc, hipStream_t stream);
+
 hipError_t launch_gather_attend(const KvView& kv, bool paged, int group, const uint16_t* q,
                                 const int32_t* idx, const int32_t* count, int batch, int n_q_heads,
                                 int k_max, int chunk, int n_splits, float scale, float* part,

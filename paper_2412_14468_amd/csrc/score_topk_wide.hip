@@ -1,0 +1,323 @@
+// SCORE + TOPK for signatures wider than 32 bits (b = 32 W bits, W = 2, 4, 8, 16; the bit-width
+// ablation of section 5.3 and the SCORE latency table of the appendix) for gfx950.
+//
+// Same two launches and the same tables as the 32-bit kernels (score_topk.hip): a block of 16
+// waves owns 16 consecutive units of one KV head and serves its G query heads; score_hist leaves
+// one row of cumulative counts C(s) = #{score >= s}, s = 0..b, per block and head; topk_select
+// sums the rows, finds the threshold T and the tie quota, and writes the ids in token order.
+// What differs: a code is W words, the score b - sum of popcounts has b + 1 values, and a lane
+// handles one token at a time (a wave walks its unit 64 tokens per step), so that ranks come
+// straight from wave ballots:
+//   - the query words sit in LDS and are read as broadcasts (G W words do not fit scalar registers
+//     for the larger shapes); popcount accumulates in the instruction's add operand;
+//   - the select makes two passes over per-step ballot masks instead of two passes over the codes:
+//     the first pass scores the unit once, keeps for every 64-token step and head the masks
+//     "score > T" and "score == T" in LDS and counts them; after the waves of the block have
+//     exchanged their counts, the second pass turns masks into ranks (ties in token order against
+//     the wave's share of the quota) and stores the ids.
+// Units are 256, 512 or 1024 tokens (16 steps of masks per wave at most).
+#include "kernels.hpp"
+
+namespace ha {
+
+namespace {
+
+constexpr int kAllTies = 0x7fffffff;
+constexpr int kWpb = kTopkWavesPerBlock;
+constexpr int kThreads = kWpb * kWave;
+constexpr int kMaxSteps = 16;                 // 64-token steps per unit: units of at most 1024 tokens
+
+__host__ __device__ constexpr int bins_of(int W) { return 32 * W + 1; }
+// LDS histogram copies per bin: as many as fit about 32 KiB, a power of two, at most 32
+__host__ __device__ constexpr int copies_of(int G, int W)
+{
+    int c = 32;
+    while (c > 1 && G * bins_of(W) * c > 8192) c /= 2;
+    return c;
+}
+
+template <int W>
+struct CodeWords {
+    uint32_t w[W];
+};
+
+// the W words of token t (one lane, one token); pointer arithmetic in words
+template <bool PAGED, int W>
+__device__ __forceinline__ CodeWords<W> load_code(const KvView& c, int b, int kvh, int t)
+{
+    CodeWords<W> r;
+    const uint32_t* p = c.codes + row_of<PAGED>(c, b, kvh, t) * W;
+    if constexpr (W == 2) {
+        const uint2 x = *reinterpret_cast<const uint2*>(p);
+        r.w[0] = x.x; r.w[1] = x.y;
+    } else {
+#pragma unroll
+        for (int i = 0; i < W / 4; ++i) {
+            const uint4 x = reinterpret_cast<const uint4*>(p)[i];
+            r.w[4 * i] = x.x; r.w[4 * i + 1] = x.y; r.w[4 * i + 2] = x.z; r.w[4 * i + 3] = x.w;
+        }
+    }
+    return r;
+}
+
+// similarity b - Hamming distance = number of agreeing bits
+template <int W>
+__device__ __forceinline__ int similarity(const CodeWords<W>& k, const uint32_t* __restrict__ q)
+{
+    int s = 0;
+#pragma unroll
+    for (int i = 0; i < W; ++i) s += __popc(~(k.w[i] ^ q[i]));
+    return s;
+}
+
+// blk_cum rows have 32 W + 2 ints: C(0..b) and a zero, so that "row[T + 1]" is valid for T = b
+template <int G, bool PAGED, int W>
+__global__ __launch_bounds__(kThreads) void score_hist_wide_kernel(KvView c, const uint32_t* __restrict__ q_codes,
+                                                                   int n_q_heads, int n_cap, int unit_tokens,
+                                                                   int n_sink, int n_local, int blocks_pitch,
+                                                                   int32_t* __restrict__ blk_cum)
+{
+    constexpr int kBinsW = bins_of(W), kRow = kBinsW + 1, kCopiesW = copies_of(G, W);
+    constexpr int kPerLane = (kRow + kWave - 1) / kWave;          // bins a lane owns in the final scan
+    __shared__ unsigned hist[G * kBinsW * kCopiesW];                 // [head][score][copy]
+    __shared__ int bsum[G * kRow];
+    __shared__ uint32_t qs[G * W];
+    const int tid = threadIdx.x, wave = uniform(tid >> 6), lane = tid & 63;
+    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int bx = rotated_block(blockIdx.x, kvh + b, gridDim.x);
+    const int n = min(c.seq_lens[b], n_cap);
+    if ((int64_t)bx * kWpb * unit_tokens >= n) return;
+    const int64_t t_begin = ((int64_t)bx * kWpb + wave) * unit_tokens;
+    const int t_end = (int)min((int64_t)n, t_begin + unit_tokens);
+    const int lo = min(n_sink, n), hi = max(lo, n - n_local);       // only tokens in [lo, hi) are scored
+    for (int i = tid; i < G * kBinsW * kCopiesW; i += kThreads) hist[i] = 0u;
+    for (int i = tid; i < G * kRow; i += kThreads) bsum[i] = 0;
+    if (tid < G * W) qs[tid] = q_codes[((int64_t)b * n_q_heads + kvh * G) * W + tid];
+    __syncthreads();
+
+    unsigned* mine = hist + (lane & (kCopiesW - 1));
+    for (int64_t base = t_begin; base < t_end; base += kWave) {
+        const int t = (int)base + lane;
+        if (t >= lo && t < min(t_end, hi)) {
+            const CodeWords<W> k = load_code<PAGED, W>(c, b, kvh, t);
+#pragma unroll
+            for (int j = 0; j < G; ++j)
+                atomicAdd(&mine[(j * kBinsW + similarity<W>(k, qs + j * W)) * kCopiesW], 1u);
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < G * kBinsW; i += kThreads) {
+        int s = 0;
+#pragma unroll
+        for (int cp = 0; cp < kCopiesW; ++cp) s += (int)hist[i * kCopiesW + cp];
+        bsum[(i / kBinsW) * kRow + i % kBinsW] = s;
+    }
+    __syncthreads();
+    // cumulative counts from the top: lane L owns bins L * kPerLane .. + kPerLane - 1 of head `wave`
+    for (int j = wave; j < G; j += kWpb) {
+        int h[kPerLane], mine_sum = 0;
+#pragma unroll
+        for (int i = 0; i < kPerLane; ++i) {
+            const int s = lane * kPerLane + i;
+            h[i] = s < kBinsW ? bsum[j * kRow + s] : 0;
+            mine_sum += h[i];
+        }
+        const int incl = wave_incl_scan_i32(mine_sum);
+        const int total = __builtin_amdgcn_readlane(incl, 63);
+        int above = total - incl;                                  // counts of all bins owned by higher lanes
+        const int64_t bh = (int64_t)b * n_q_heads + kvh * G + j;
+        int32_t* row = blk_cum + (bh * blocks_pitch + bx) * kRow;
+#pragma unroll
+        for (int i = kPerLane - 1; i >= 0; --i) {
+            const int s = lane * kPerLane + i;
+            above += h[i];
+            if (s < kRow) row[s] = above;                          // slot b + 1 gets 0
+        }
+    }
+}
+
+template <int G, bool PAGED, int W>
+__global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, const uint32_t* __restrict__ q_codes,
+                                                                    const int32_t* __restrict__ k_per_seq, int k_max,
+                                                                    int n_sink, int n_local, int pitch, int n_q_heads,
+                                                                    int n_cap, int unit_tokens, int blocks_pitch,
+                                                                    const int32_t* __restrict__ blk_cum,
+                                                                    int32_t* __restrict__ idx, int32_t* __restrict__ count,
+                                                                    uint8_t* __restrict__ threshold)
+{
+    constexpr int kBinsW = bins_of(W), kRow = kBinsW + 1;
+    __shared__ int tot[G * kRow];
+    __shared__ int thr[G], posb[G], quotab[G];
+    __shared__ int wgt[kWpb][G], weq[kWpb][G];                     // per wave: tokens taken for sure / tied
+    __shared__ uint64_t m_gt[kWpb][kMaxSteps][G], m_eq[kWpb][kMaxSteps][G];
+    __shared__ uint32_t qs[G * W];
+    const int tid = threadIdx.x, wave = uniform(tid >> 6), lane = tid & 63;
+    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int bx = rotated_block(blockIdx.x, kvh + b, gridDim.x);
+    const int64_t bh0 = (int64_t)b * n_q_heads + kvh * G;
+    const int n = min(c.seq_lens[b], n_cap);
+    const int k_raw = k_per_seq ? k_per_seq[b] : k_max;
+    const int lo = min(n_sink, n), hi = max(lo, n - n_local);
+    const int k = max(0, min(k_raw, min(k_max, hi - lo)));
+    const bool nothing = k == 0 && lo == 0 && hi == n;
+    const int block_tokens = kWpb * unit_tokens;
+    if (bx > 0 && ((int64_t)bx * block_tokens >= n || nothing)) return;   // block 0 reports the counts
+    const int n_blocks = (n + block_tokens - 1) / block_tokens;
+    const int64_t t_begin = ((int64_t)bx * kWpb + wave) * unit_tokens;
+    const bool active = t_begin < n && !nothing;
+    const int t_end = (int)min((int64_t)n, t_begin + unit_tokens);
+
+    if (tid < G) thr[tid] = -1;
+    if (tid < G * W) qs[tid] = q_codes[bh0 * W + tid];
+    // whole-sequence cumulative counts: one thread per (head, score), blocks summed in a loop
+    for (int i = tid; i < G * kRow; i += kThreads) {
+        const int j = i / kRow, col = i - j * kRow;
+        const int32_t* p = blk_cum + (bh0 + j) * blocks_pitch * kRow + col;
+        int v = 0;
+        for (int blk = 0; blk < n_blocks; ++blk) v += p[(int64_t)blk * kRow];
+        tot[i] = v;
+    }
+    __syncthreads();
+    // threshold: the largest score s with C(s) >= k (C(0) = number of scored tokens >= k)
+    if (k > 0) {
+        for (int i = tid; i < G * kBinsW; i += kThreads) {
+            const int j = i / kBinsW, s = i - j * kBinsW;
+            if (tot[j * kRow + s] >= k) atomicMax(&thr[j], s);
+        }
+    }
+    __syncthreads();
+    for (int j = wave; j < G; j += kWpb) {
+        const int64_t bh = bh0 + j;
+        const int32_t* tab = blk_cum + bh * blocks_pitch * kRow;
+        const int T = k > 0 ? thr[j] : kBinsW;                           // k = 0: nothing reaches the threshold
+        int r = 0, gt = 0, ge = 0, own_gt = 0, own_ge = 0;
+        if (k > 0) {
+            r = k - tot[j * kRow + T + 1];
+            for (int blk = lane; blk < bx; blk += kWave) {
+                ge += tab[(int64_t)blk * kRow + T];
+                gt += tab[(int64_t)blk * kRow + T + 1];
+            }
+            own_ge = tab[(int64_t)bx * kRow + T];
+            own_gt = tab[(int64_t)bx * kRow + T + 1];
+        }
+        gt = wave_sum_i32(gt);
+        ge = wave_sum_i32(ge);
+        if (lane == 0) {
+            const int eq_before = ge - gt, own_eq = own_ge - own_gt, left = r - eq_before;
+            const int bs = (int)min((int64_t)n, (int64_t)bx * block_tokens);   // always-kept tokens before this block
+            thr[j] = T;
+            posb[j] = gt + min(eq_before, r) + min(lo, bs) + max(0, bs - hi);
+            quotab[j] = left >= own_eq ? kAllTies : max(left, 0);
+            if (bx == 0) {
+                count[bh] = lo + k + (n - hi);
+                if (threshold) threshold[bh] = (uint8_t)(k > 0 ? min(T, 255) : 0);   // saturates for b >= 256
+            }
+        }
+    }
+    __syncthreads();
+
+    // ---- pass 1: score the unit once; masks per 64-token step and head, counts per wave
+    int T[G], cgt[G], ceq[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) { T[j] = uniform(thr[j]); cgt[j] = ceq[j] = 0; }
+    const int n_steps = active ? (t_end - (int)t_begin + kWave - 1) / kWave : 0;
+    for (int s = 0; s < n_steps; ++s) {
+        const int t = (int)t_begin + s * kWave + lane;
+        const bool valid = t < t_end, scored = valid && t >= lo && t < hi;
+        CodeWords<W> kc;
+#pragma unroll
+        for (int i = 0; i < W; ++i) kc.w[i] = 0u;
+        if (scored) kc = load_code<PAGED, W>(c, b, kvh, t);
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            const int sc = similarity<W>(kc, qs + j * W);
+            const uint64_t g_mask = __ballot((scored && sc > T[j]) || (valid && !scored));   // kept tokens are always taken
+            const uint64_t e_mask = __ballot(scored && sc == T[j]);
+            if (lane == 0) { m_gt[wave][s][j] = g_mask; m_eq[wave][s][j] = e_mask; }
+            cgt[j] += __popcll(g_mask);
+            ceq[j] += __popcll(e_mask);
+        }
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int j = 0; j < G; ++j) { wgt[wave][j] = cgt[j]; weq[wave][j] = ceq[j]; }
+    }
+    __syncthreads();
+    if (!active) return;
+
+    // ---- pass 2: ranks from the masks; a tie is taken while the wave's share of the quota lasts
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        const int gt_before = wave_sum_i32(lane < wave ? wgt[lane][j] : 0);
+        const int eq_before = wave_sum_i32(lane < wave ? weq[lane][j] : 0);
+        const int quota_b = uniform(quotab[j]);
+        const int quota_w = quota_b == kAllTies ? kAllTies : max(0, quota_b - eq_before);
+        int start = uniform(posb[j]) + gt_before + min(eq_before, quota_b);
+        int seen = 0;
+        int32_t* out = idx + (bh0 + j) * pitch;
+        for (int s = 0; s < n_steps; ++s) {
+            const uint64_t g_mask = m_gt[wave][s][j], e_mask = m_eq[wave][s][j];
+            const bool tie = (e_mask >> lane) & 1ull;
+            const bool take = ((g_mask >> lane) & 1ull) || (tie && seen + lanes_below(e_mask) < quota_w);
+            const uint64_t t_mask = __ballot(take);
+            const int rank = start + lanes_below(t_mask);
+            if (take && rank < pitch) out[rank] = (int)t_begin + s * kWave + lane;
+            start += __popcll(t_mask);
+            seen += __popcll(e_mask);
+        }
+    }
+}
+
+template <int G, bool PAGED, int W>
+hipError_t launch_w(const KvView& kv, const TopkCall& a, int unit_tokens, const TopkScratch& sc, hipStream_t stream)
+{
+    const int64_t block_tokens = (int64_t)kWpb * unit_tokens;
+    int n_blocks = (int)((a.max_seq_len + block_tokens - 1) / block_tokens);
+    if (n_blocks < 1) n_blocks = 1;
+    const dim3 grid(n_blocks, kv.n_kv_heads, a.batch), block(kThreads);
+    score_hist_wide_kernel<G, PAGED, W><<<grid, block, 0, stream>>>(kv, a.q_codes, a.n_q_heads, a.max_seq_len, unit_tokens,
+                                                                   a.n_sink, a.n_local, sc.blocks_pitch, sc.blk_cum);
+    topk_select_wide_kernel<G, PAGED, W><<<grid, block, 0, stream>>>(
+        kv, a.q_codes, a.k_per_seq, a.k_max, a.n_sink, a.n_local, a.k_max + a.n_sink + a.n_local, a.n_q_heads,
+        a.max_seq_len, unit_tokens, sc.blocks_pitch, sc.blk_cum, a.idx, a.count, a.threshold);
+    return hipGetLastError();
+}
+
+template <int G, bool PAGED>
+hipError_t launch_words(int words, const KvView& kv, const TopkCall& a, int unit_tokens, const TopkScratch& sc,
+                        hipStream_t stream)
+{
+    switch (words) {
+    case 2: return launch_w<G, PAGED, 2>(kv, a, unit_tokens, sc, stream);
+    case 4: return launch_w<G, PAGED, 4>(kv, a, unit_tokens, sc, stream);
+    case 8: return launch_w<G, PAGED, 8>(kv, a, unit_tokens, sc, stream);
+    case 16: return launch_w<G, PAGED, 16>(kv, a, unit_tokens, sc, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+template <int G>
+hipError_t launch_group(bool paged, int words, const KvView& kv, const TopkCall& a, int unit_tokens,
+                        const TopkScratch& sc, hipStream_t stream)
+{
+    return paged ? launch_words<G, true>(words, kv, a, unit_tokens, sc, stream)
+                 : launch_words<G, false>(words, kv, a, unit_tokens, sc, stream);
+}
+
+}  // namespace
+
+// unit_tokens: 256, 512 or 1024
+hipError_t launch_score_topk_wide(const KvView& kv, bool paged, int group, int words, const TopkCall& call,
+                                  int unit_tokens, const TopkScratch& sc, hipStream_t stream)
+{
+    if (unit_tokens > kMaxSteps * kWave) return hipErrorInvalidValue;
+    switch (group) {
+    case 1: return launch_group<1>(paged, words, kv, call, unit_tokens, sc, stream);
+    case 2: return launch_group<2>(paged, words, kv, call, unit_tokens, sc, stream);
+    case 4: return launch_group<4>(paged, words, kv, call, unit_tokens, sc, stream);
+    case 8: return launch_group<8>(paged, words, kv, call, unit_tokens, sc, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace ha

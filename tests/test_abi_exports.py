@@ -30,7 +30,7 @@ def test_create_rejects_bad_shapes_before_touching_the_device():
     h = C.c_void_p()
     cases = [
         (Config(64, 32, 8, 32, 0, 1, 1024, 32), ha.UNSUPPORTED, "head_dim"),
-        (Config(128, 32, 8, 64, 0, 1, 1024, 32), ha.UNSUPPORTED, "bits"),
+        (Config(128, 32, 8, 48, 0, 1, 1024, 32), ha.UNSUPPORTED, "bits"),
         (Config(128, 32, 5, 32, 0, 1, 1024, 32), ha.INVALID_ARG, "multiple"),
         (Config(128, 48, 16, 32, 0, 1, 1024, 32), ha.UNSUPPORTED, "group"),
         (Config(128, 32, 8, 32, 8, 1, 1024, 32), ha.UNSUPPORTED, "page_size"),

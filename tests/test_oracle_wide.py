@@ -34,6 +34,7 @@ def test_score_wide_law_of_uniform_codes():
     q = rng.integers(0, 2 ** 32, size=words, dtype=np.uint64).astype(np.uint32)
     ks = rng.integers(0, 2 ** 32, size=(20000, words), dtype=np.uint64).astype(np.uint32)
     sc = oracle.scores_wide(q, ks)
+    assert all(int(sc[i]) == oracle.score_wide(q, ks[i]) for i in range(0, 20000, 997))
     assert abs(sc.mean() - 64.0) < 0.2 and abs(sc.var() - 32.0) < 1.5        # Binomial(128, 1/2)
 
 
