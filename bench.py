@@ -327,16 +327,28 @@ def main():
         cpu = {"value": round(alg_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "us_per_layer_step": round(cpu_s * 1e6, 1),
                "cores": oracle.num_threads(), "kind": "oracle",
                "sample": f"whole {cfg.name} layer-step (all {B * Hq} (sequence, head) pairs), median of {len(times)} runs"}
-        # parity of ring layer 0 against the oracle (outputs only; tests/ hold the full staged checks)
+        # parity of ring layer 0 against the oracle, staged as in tests/: the GPU's own codes are compared
+        # bit by bit (they may differ where the pre-sign activation is within rounding of 0), then SCORE +
+        # TOPK + GATHER-ATT run on the oracle's codes, where index sets must be identical
         s0 = layers[0]
-        runner.decode_step(ctx, s0)
+        runner.build_key_codes(ctx, s0)
+        ctx.hashattn_encode_query(s0.phi_q, s0.q, s0.B, s0.q_codes)
+        torch.cuda.synchronize()
+        gpu_codes = s0.codes.cpu().numpy().view(np.uint32)
+        diff_bits = int(sum(bin(int(x)).count("1") for x in (gpu_codes ^ codes)[gpu_codes != codes]))
+        q_same = bool(np.array_equal(s0.q_codes.cpu().numpy().view(np.uint32), res["q_codes"]))
+        s0.codes.copy_(torch.from_numpy(codes.view(np.int32)).to("cuda:0"))
+        s0.q_codes.copy_(torch.from_numpy(res["q_codes"].view(np.int32)).to("cuda:0"))
+        runner.score_topk(ctx, s0)
+        runner.gather_attend(ctx, s0)
         torch.cuda.synchronize()
         got = s0.out.float().cpu().numpy().astype(np.float64)
         n_att = int(res["count"].max())
         same_sets = bool(np.array_equal(s0.count.cpu().numpy(), res["count"]) and
                          np.array_equal(s0.idx.cpu().numpy()[:, :, :n_att], res["idx"][:, :, :n_att]))
         err = np.abs(got - res["out"])
-        parity = {"index_sets_equal": same_sets,
+        parity = {"key_code_bits_differing": diff_bits, "key_code_bits_total": int(codes.size) * 32,
+                  "query_codes_equal": q_same, "index_sets_equal_on_oracle_codes": same_sets,
                   "out_within_tol": bool(np.all(err <= 2e-3 + 1e-2 * np.abs(res["out"]))) if same_sets else None,
                   "max_abs_err": float(err.max()) if same_sets else None}
 
