@@ -132,7 +132,7 @@ int pick_unit_tokens(const hashattn_ctx* ctx, int batch, int max_seq_len, bool m
     const int cap = (mixed || ctx->cfg.bits > 32) ? kMaxUnit / 2 : kMaxUnit;      // wide codes: units of at most 1024
     int unit = kMinUnit;
     auto blocks = [&](int u) { return (max_seq_len + (int64_t)u * ha::kTopkWavesPerBlock - 1) / ((int64_t)u * ha::kTopkWavesPerBlock); };
-    // a 16-wave block fills a CU: prefer one round of blocks over the 256 CUs
+    // two 8-wave blocks share a CU; up to about one block per CU keeps the per-block tables short
     while (unit < cap && lanes * blocks(unit) > 256) unit *= 2;
     // never more blocks per sequence than the scratch pitch
     while (unit < (ctx->cfg.bits > 32 ? kMaxUnit / 2 : kMaxUnit) && blocks(unit) > ctx->blocks_pitch) unit *= 2;
@@ -205,7 +205,7 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
     if (e != hipSuccess) { delete ctx; return fail(nullptr, HASHATTN_HIP_ERROR, "create: hipGetDevice: %s", hipGetErrorString(e)); }
 
     const int64_t bh = (int64_t)cfg->max_batch * cfg->n_q_heads;
-    // per-block score tables: one block per 16 units of at least 256 tokens, at most kMaxTopkBlocks per sequence
+    // per-block score tables: one block per 8 units of at least 256 tokens, at most kMaxTopkBlocks per sequence
     int64_t pitch = (cfg->max_context + (int64_t)kMinUnit * ha::kTopkWavesPerBlock - 1) / ((int64_t)kMinUnit * ha::kTopkWavesPerBlock);
     if (pitch > ha::kMaxTopkBlocks) pitch = ha::kMaxTopkBlocks;
     ctx->blocks_pitch = (int32_t)pitch;

@@ -11,8 +11,8 @@ constexpr int kBins = 33;         // Hamming similarity takes values 0..32
 constexpr int kCumRow = 34;       // row of cumulative score counts: bins 0..32 and a zero slot
 constexpr int kPage = 16;         // tokens per page in the paged layout
 constexpr int kWave = 64;
-constexpr int kTopkWavesPerBlock = 16;   // SCORE/TOPK: units (waves) per block
-constexpr int kMaxTopkBlocks = 128;      // SCORE/TOPK: most blocks per sequence (every block sums the per-block tables)
+constexpr int kTopkWavesPerBlock = 8;    // SCORE/TOPK: units (waves) per block
+constexpr int kMaxTopkBlocks = 256;      // SCORE/TOPK: most blocks per sequence (every block sums the per-block tables)
 constexpr int kPartStride = 132;  // floats per split partial: acc[128], m, l, pad
 
 // Plain view of the caller's KV cache, passed to kernels by value.

@@ -14,7 +14,7 @@ struct MlpView {
 };
 
 struct TopkScratch {
-    int32_t* blk_cum;      // [B][Hq][blocks_pitch][34]: per block of 16 units, #{score >= s}
+    int32_t* blk_cum;      // [B][Hq][blocks_pitch][34]: per block of 8 units, #{score >= s}
     int32_t blocks_pitch;
 };
 

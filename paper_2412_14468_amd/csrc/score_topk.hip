@@ -3,7 +3,7 @@
 // The score of a token is the Hamming similarity 32 - popcount(q_code ^ k_code),
 // an integer in 0..32, so top-k is a 33-bin counting select in two launches.
 // A sequence is cut into "units" (contiguous runs of tokens, one per wave); a block
-// of 16 waves owns 16 consecutive units of one KV head and serves the G query heads
+// of 8 waves owns 8 consecutive units of one KV head and serves the G query heads
 // of its group from one read of the codes.
 //   1. score_hist   every wave scores its unit for the G heads and counts scores per
 //                   head in one LDS histogram per block.  A bin has 32 copies, picked
@@ -78,7 +78,7 @@ __device__ __forceinline__ void count_chunk(const uint4 (&cw)[4], int base, int 
 
 // Table written by score_hist and read by topk_select; a row holds #{score >= s} for s = 0..32 and
 // a zero in slot 33, so that "row[T + 1]" is valid for T = 32:
-//   blk_cum:  [B][Hq][blocks_pitch][34] ints, one row per block of 16 units
+//   blk_cum:  [B][Hq][blocks_pitch][34] ints, one row per block of 8 units
 template <int G, bool PAGED>
 __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const uint32_t* __restrict__ q_codes,
                                                               int n_q_heads, int n_cap, int unit_tokens,
@@ -270,11 +270,12 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
     const int n_raw = c.seq_lens[b];
     const int k_raw = k_per_seq ? k_per_seq[b] : k_max;
     const int srow = tid / kCumRow, scol = tid - srow * kCumRow;
-    int tv[G][2];
+    constexpr int kPrefetch = 3;                                // passes of table rows requested up front
+    int tv[G][kPrefetch];
 #pragma unroll
     for (int j = 0; j < G; ++j)
 #pragma unroll
-        for (int u = 0; u < 2; ++u) {
+        for (int u = 0; u < kPrefetch; ++u) {
             const int blk = srow + u * kRowsPerPass;
             tv[j][u] = 0;
             if (srow < kRowsPerPass && blk < nb_cap)
@@ -317,9 +318,9 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
         for (int j = 0; j < G; ++j) {
             int v = 0;
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
+            for (int u = 0; u < kPrefetch; ++u)
                 if (srow + u * kRowsPerPass < n_blocks) v += tv[j][u];
-            for (int blk = srow + 2 * kRowsPerPass; blk < n_blocks; blk += kRowsPerPass)      // very long contexts
+            for (int blk = srow + kPrefetch * kRowsPerPass; blk < n_blocks; blk += kRowsPerPass)   // very long contexts
                 v += blk_cum[((bh0 + j) * blocks_pitch + blk) * kCumRow + scol];
             if (v) atomicAdd(&tot[j * kCumRow + scol], v);
         }

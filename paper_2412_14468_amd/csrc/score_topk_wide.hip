@@ -1,8 +1,8 @@
 // SCORE + TOPK for signatures wider than 32 bits (b = 32 W bits, W = 2, 4, 8, 16; the bit-width
 // ablation of section 5.3 and the SCORE latency table of the appendix) for gfx950.
 //
-// Same two launches and the same tables as the 32-bit kernels (score_topk.hip): a block of 16
-// waves owns 16 consecutive units of one KV head and serves its G query heads; score_hist leaves
+// Same two launches and the same tables as the 32-bit kernels (score_topk.hip): a block of 8
+// waves owns 8 consecutive units of one KV head and serves its G query heads; score_hist leaves
 // one row of cumulative counts C(s) = #{score >= s}, s = 0..b, per block and head; topk_select
 // sums the rows, finds the threshold T and the tie quota, and writes the ids in token order.
 // What differs: a code is W words, the score b - sum of popcounts has b + 1 values, and a lane
