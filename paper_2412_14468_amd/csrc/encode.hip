@@ -148,24 +148,25 @@ __device__ __forceinline__ void fetch_weights(const float* __restrict__ W, float
     for (int i = 0; i < SPAN; ++i) w[i] = W[(int64_t)(p * SPAN + i) * DOUT + j];
 }
 
-template <int DI, int DOUT>
+// VT: vectors of the block that are worked on (slots VT.. of `in` and `out` are left alone)
+template <int DI, int DOUT, int VT>
 __device__ __forceinline__ void gemv_layer(const float (&w)[DI * DOUT / 256], const float* __restrict__ bias,
                                            const float (*in)[kMaxWidth], float (*out)[kMaxWidth], float* red,
                                            bool last)
 {
     constexpr int SPAN = DI * DOUT / 256, PARTS = 256 / DOUT;
     const int tid = threadIdx.x, j = tid % DOUT, p = tid / DOUT;
-    float acc[kVecPerBlock];
+    float acc[VT];
 #pragma unroll
-    for (int v = 0; v < kVecPerBlock; ++v) acc[v] = 0.f;
+    for (int v = 0; v < VT; ++v) acc[v] = 0.f;
 #pragma unroll
     for (int i = 0; i < SPAN; ++i)
 #pragma unroll
-        for (int v = 0; v < kVecPerBlock; ++v) acc[v] = fmaf(in[v][p * SPAN + i], w[i], acc[v]);
+        for (int v = 0; v < VT; ++v) acc[v] = fmaf(in[v][p * SPAN + i], w[i], acc[v]);
 #pragma unroll
-    for (int v = 0; v < kVecPerBlock; ++v) red[(p * kVecPerBlock + v) * DOUT + j] = acc[v];
+    for (int v = 0; v < VT; ++v) red[(p * kVecPerBlock + v) * DOUT + j] = acc[v];
     __syncthreads();
-    for (int o = tid; o < kVecPerBlock * DOUT; o += 256) {
+    for (int o = tid; o < VT * DOUT; o += 256) {
         const int v = o / DOUT, jj = o - v * DOUT;
         float z = 0.f;
 #pragma unroll
@@ -177,7 +178,9 @@ __device__ __forceinline__ void gemv_layer(const float (&w)[DI * DOUT / 256], co
 }
 
 // NL layers: 128 -> D1 -> D2 -> 32 (NL = 3), 128 -> D1 -> 32 (NL = 2), 128 -> 32 (NL = 1).
-template <int MODE, bool PAGED, int NL, int D1, int D2>
+// VT = 1 when the block has a single vector (one query per head at batch 1): the other seven slots
+// would cost seven times the LDS reads and multiplies for nothing.
+template <int MODE, bool PAGED, int NL, int D1, int D2, int VT>
 __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int n_heads,
                                                                const uint16_t* __restrict__ x,
                                                                const uint16_t* __restrict__ v_new, int n_vec,
@@ -198,11 +201,11 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
     if constexpr (NL == 3) fetch_weights<I2, kBits>(phi.W[2] + (int64_t)head * I2 * kBits, w2);
     load_vectors<MODE>(act[0], n_heads, head, v0, x, n_vec, n_new);
     __syncthreads();
-    gemv_layer<kHeadDim, O0>(w0, phi.bias[0] ? phi.bias[0] + (int64_t)head * O0 : nullptr, act[0], act[1], red, NL == 1);
+    gemv_layer<kHeadDim, O0, VT>(w0, phi.bias[0] ? phi.bias[0] + (int64_t)head * O0 : nullptr, act[0], act[1], red, NL == 1);
     if constexpr (NL >= 2)
-        gemv_layer<I1, O1>(w1, phi.bias[1] ? phi.bias[1] + (int64_t)head * O1 : nullptr, act[1], act[0], red, NL == 2);
+        gemv_layer<I1, O1, VT>(w1, phi.bias[1] ? phi.bias[1] + (int64_t)head * O1 : nullptr, act[1], act[0], red, NL == 2);
     if constexpr (NL == 3)
-        gemv_layer<I2, kBits>(w2, phi.bias[2] ? phi.bias[2] + (int64_t)head * kBits : nullptr, act[0], act[1], red, true);
+        gemv_layer<I2, kBits, VT>(w2, phi.bias[2] ? phi.bias[2] + (int64_t)head * kBits : nullptr, act[0], act[1], red, true);
     store_codes<MODE, PAGED>(act[NL & 1], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap);
 }
 
@@ -213,12 +216,18 @@ void launch_encode_vec(const MlpView& phi, dim3 grid, int n_heads, const uint16_
     const int nl = phi.n_layers, d1 = phi.dims[1], d2 = phi.dims[2];
     if (phi.dims[nl] != kBits)           // wider signatures: the general kernel
         encode_vec_kernel<MODE, PAGED><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+    else if (nl == 1 && n_vec == 1)
+        encode_vec_fixed_kernel<MODE, PAGED, 1, 32, 32, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
     else if (nl == 1)
-        encode_vec_fixed_kernel<MODE, PAGED, 1, 32, 32><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+        encode_vec_fixed_kernel<MODE, PAGED, 1, 32, 32, kVecPerBlock><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+    else if (nl == 2 && d1 == 128 && n_vec == 1)
+        encode_vec_fixed_kernel<MODE, PAGED, 2, 128, 32, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
     else if (nl == 2 && d1 == 128)
-        encode_vec_fixed_kernel<MODE, PAGED, 2, 128, 32><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+        encode_vec_fixed_kernel<MODE, PAGED, 2, 128, 32, kVecPerBlock><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+    else if (nl == 3 && d1 == 128 && d2 == 128 && n_vec == 1)
+        encode_vec_fixed_kernel<MODE, PAGED, 3, 128, 128, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
     else if (nl == 3 && d1 == 128 && d2 == 128)
-        encode_vec_fixed_kernel<MODE, PAGED, 3, 128, 128><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+        encode_vec_fixed_kernel<MODE, PAGED, 3, 128, 128, kVecPerBlock><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
     else
         encode_vec_kernel<MODE, PAGED><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
 }
