@@ -118,20 +118,36 @@ __device__ __forceinline__ void write_output(const float* st, float* red, uint16
     }
 }
 
-// Whole block: out = sum_s acc_s 2^(m_s - M) / sum_s l_s 2^(m_s - M) over `used` partials, to bf16.
+// Whole block: out = sum_s acc_s 2^(m_s - M) / sum_s l_s 2^(m_s - M) over the first `used` of the
+// n_slots partials, to bf16; used = min(n_slots, ceil(min(*len_ptr, len_cap) / chunk)).
+// All n_slots slots are memory of the scratch buffer, so m, l and the first sixteen partials are
+// requested before the length has arrived (one trip to memory instead of three); what lies past
+// `used` may be stale and is masked, never multiplied.
 // lds: at least 2 * kMaxSplits + 8 floats.  Every thread of the block must call it.
-__device__ __forceinline__ void merge_partials_block(const float* __restrict__ p, int used,
+__device__ __forceinline__ void merge_partials_block(const float* __restrict__ p, int n_slots,
+                                                     const int32_t* __restrict__ len_ptr, int len_cap, int chunk,
                                                      uint16_t* __restrict__ out, float* lds)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     float* w = lds;                       // [kMaxSplits] weights 2^(m_s - M)
     float* red = lds + kMaxSplits;        // [8]
     float* half = lds + kMaxSplits + 8;   // [128]
+    const int ch = tid & (kHeadDim - 1), h = tid >> 7;       // two thread halves take alternate partials
+    const int len_raw = *len_ptr;
     float my_m = kNegInf, my_l = 0.f;
-    if (tid < used) {
+    if (tid < n_slots) {
         my_m = p[tid * kPartStride + kHeadDim];
         my_l = p[tid * kPartStride + kHeadDim + 1];
     }
+    float v0[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int s = h + 2 * u;
+        v0[u] = s < n_slots ? p[s * kPartStride + ch] : 0.f;
+    }
+    const int used = min(n_slots, (min(len_raw, len_cap) + chunk - 1) / chunk);
+    if (tid >= used) { my_m = kNegInf; my_l = 0.f; }
+
     float M = my_m;
     for (int o = 32; o > 0; o >>= 1) M = fmaxf(M, __shfl_xor(M, o, kWave));
     if (lane == 0) red[wave] = M;
@@ -145,9 +161,13 @@ __device__ __forceinline__ void merge_partials_block(const float* __restrict__ p
     __syncthreads();
     den = (red[4] + red[5]) + (red[6] + red[7]);
 
-    const int ch = tid & (kHeadDim - 1), h = tid >> 7;       // two thread halves take alternate partials
     float num = 0.f;
-    int s = h;
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+        const int s = h + 2 * u;
+        if (s < used) num = fmaf(v0[u], w[s], num);
+    }
+    int s = h + 16;
 #pragma unroll 1
     for (; s + 14 < used; s += 16) {
         float v[8];
@@ -399,9 +419,8 @@ __global__ __launch_bounds__(256) void merge_partials_kernel(const float* __rest
     __shared__ float lds[2 * kMaxSplits + 8];
     const int hq = blockIdx.x, b = blockIdx.y;
     const int64_t bh = (int64_t)b * n_q_heads + hq;
-    const int len = min(PER_HEAD ? lens[bh] : lens[b], len_cap);
-    const int used = min(n_splits, (len + chunk - 1) / chunk);
-    merge_partials_block(part + bh * n_splits * kPartStride, used, out + bh * kHeadDim, lds);
+    merge_partials_block(part + bh * n_splits * kPartStride, n_splits, PER_HEAD ? lens + bh : lens + b, len_cap, chunk,
+                         out + bh * kHeadDim, lds);
 }
 
 constexpr float kLog2e = 1.4426950408889634f;
