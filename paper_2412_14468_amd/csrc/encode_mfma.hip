@@ -36,7 +36,8 @@ typedef __attribute__((ext_vector_type(2))) float f32x2;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
 constexpr int kTileTokens = 32;
-constexpr int kMfmaThreads = 512;
+// waves per block: three per SIMD where the registers allow it (up to two layers), else two
+__host__ __device__ constexpr int mfma_threads(int n_layers) { return n_layers <= 2 ? 768 : 512; }
 constexpr int kFragQuads = 64;          // a fragment: 64 lanes x 16 bytes
 constexpr float kLog2eF = 1.4426950408889634f;
 
@@ -139,6 +140,15 @@ __device__ __forceinline__ void layer_tile(const uint4* __restrict__ frags, cons
 #pragma unroll
             for (int m = 0; m < M; ++m) { a_hi[m] = n_hi[m]; a_lo[m] = n_lo[m]; }
         }
+        // order inside the step: one LDS read of the next fragments after each multiply, so that the
+        // reads are spread under the matrix pipe instead of bunched at the end of the step
+        if (s < 7) {
+#pragma unroll
+            for (int i = 0; i < 2 * M; ++i) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);     // one MFMA
+                __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);     // one LDS read
+            }
+        }
         __builtin_amdgcn_sched_barrier(0);
     }
 }
@@ -173,11 +183,12 @@ __device__ __forceinline__ void activate_split(const f32x16 (&acc)[4], uint4 (&b
 //   from_end = 0: the n_new tokens starting at len (rows just appended, seq_lens not yet bumped)
 // A block takes block_tokens consecutive tokens of one (sequence, head).
 template <bool PAGED, int NL>
-__global__ __launch_bounds__(kMfmaThreads) void encode_bulk_mfma_kernel(KvView c, const uint4* __restrict__ frag_store,
+__global__ __launch_bounds__(mfma_threads(NL)) void encode_bulk_mfma_kernel(KvView c, const uint4* __restrict__ frag_store,
                                                                         int64_t quads_per_head, int n_cap, int64_t n_new,
                                                                         int from_end, int block_tokens)
 {
     extern __shared__ uint4 lds[];                         // this head's fragments, then its biases
+    constexpr int kMfmaThreads = mfma_threads(NL);
     constexpr int kQuads = head_bytes(NL) / 16;
     const int tid = threadIdx.x, wave = uniform(tid >> 6), lane = tid & 63, g = lane >> 5, tl = lane & 31;
     const int head = blockIdx.y, b = blockIdx.z;
@@ -247,7 +258,7 @@ hipError_t launch_nl(bool setup_only, const KvView& kv, const EncodeScratch& sc,
     int block_tokens = 256;
     while (block_tokens < 4096 && lanes * ((span + block_tokens - 1) / block_tokens) > 1024) block_tokens *= 2;
     const dim3 grid((unsigned)((span + block_tokens - 1) / block_tokens), kv.n_kv_heads, batch);
-    encode_bulk_mfma_kernel<PAGED, NL><<<grid, kMfmaThreads, lds, stream>>>(kv, sc.frags, sc.quads_per_head, max_seq_len,
+    encode_bulk_mfma_kernel<PAGED, NL><<<grid, mfma_threads(NL), lds, stream>>>(kv, sc.frags, sc.quads_per_head, max_seq_len,
                                                                            n_new, from_end, block_tokens);
     return hipSuccess;
 }
