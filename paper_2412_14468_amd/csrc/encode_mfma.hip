@@ -65,27 +65,32 @@ __host__ __device__ constexpr int head_bytes(int n_layers)
 }
 
 // Weights of one head, fp32 [in][out] per layer, to bf16 hi/lo fragments; biases (or zeros) behind them.
+// grid (heads, slices): consecutive threads read consecutive output units of one input row (coalesced),
+// one read gives the hi and the lo element.
 __global__ __launch_bounds__(256) void mlp_fragments_kernel(MlpView phi, uint4* __restrict__ out, int64_t quads_per_head)
 {
     const int head = blockIdx.x, NL = phi.n_layers;
+    const int t0 = blockIdx.y * 256 + threadIdx.x, stride = gridDim.y * 256;
     uint16_t* dst = reinterpret_cast<uint16_t*>(out + head * quads_per_head);
     int frag0 = 0, unit0 = 0;
     for (int l = 0; l < NL; ++l) {
         const int din = phi.dims[l], dout = phi.dims[l + 1], M = dout / 32;
         const float* W = phi.W[l] + (int64_t)head * din * dout;
-        const int n_elem = 2 * M * 8 * 64 * 8;
-        for (int e = threadIdx.x; e < n_elem; e += 256) {
-            const int j = e & 7, lane = (e >> 3) & 63, s = (e >> 9) & 7, m = (e >> 12) % M, pass = (e >> 12) / M;
-            const int g = lane >> 5, o = 32 * m + (lane & 31);
+        const int n_elem = M * 8 * 16 * 32;                  // (tile m, step s, slot kk = 8 g + j, unit lane ol)
+        for (int e = t0; e < n_elem; e += stride) {
+            const int ol = e & 31, kk = (e >> 5) & 15, s = (e >> 9) & 7, m = e >> 12;
+            const int g = kk >> 3, j = kk & 7, o = 32 * m + ol;
             const int k_in = l == 0 ? 64 * g + 8 * s + j
                                     : 32 * (s >> 1) + 16 * (s & 1) + 8 * (j >> 2) + 4 * g + (j & 3);
             const float w = W[(int64_t)k_in * dout + o];
             const uint32_t hi = f32_to_bf16(w);
             const uint32_t lo = f32_to_bf16(w - __uint_as_float(hi << 16));
-            dst[(int64_t)frag0 * 512 + e] = (uint16_t)(pass ? lo : hi);
+            const int within = (32 * g + ol) * 8 + j;        // lane 32 g + ol, element j
+            dst[(int64_t)(frag0 + (0 * M + m) * 8 + s) * 512 + within] = (uint16_t)hi;
+            dst[(int64_t)(frag0 + (1 * M + m) * 8 + s) * 512 + within] = (uint16_t)lo;
         }
         float* bdst = reinterpret_cast<float*>(dst + (int64_t)total_frags(NL) * 512) + unit0;
-        for (int u = threadIdx.x; u < dout; u += 256) bdst[u] = phi.bias[l] ? phi.bias[l][(int64_t)head * dout + u] : 0.f;
+        for (int u = t0; u < dout; u += stride) bdst[u] = phi.bias[l] ? phi.bias[l][(int64_t)head * dout + u] : 0.f;
         frag0 += 2 * M * 8;
         unit0 += dout;
     }
@@ -302,7 +307,7 @@ hipError_t launch_encode_bulk_mfma(const MlpView& phi, const KvView& kv, bool pa
                                    int64_t n_new, int max_seq_len, int from_end, const EncodeScratch& sc,
                                    hipStream_t stream)
 {
-    mlp_fragments_kernel<<<kv.n_kv_heads, 256, 0, stream>>>(phi, sc.frags, sc.quads_per_head);
+    mlp_fragments_kernel<<<dim3(kv.n_kv_heads, 16), 256, 0, stream>>>(phi, sc.frags, sc.quads_per_head);
     const hipError_t e = paged ? launch_paged<true>(false, phi.n_layers, kv, sc, batch, span, n_new, max_seq_len, from_end, stream)
                                : launch_paged<false>(false, phi.n_layers, kv, sc, batch, span, n_new, max_seq_len, from_end, stream);
     return e != hipSuccess ? e : hipGetLastError();
