@@ -7,18 +7,19 @@
 // merges the partials of a head and rounds to bf16.  Short lists with many heads
 // skip the split: one 16-wave block per head writes the output itself (with few
 // heads that is slower: one CU pulls only about 30 GB/s of scattered rows).
-// (Merging in the block that
-// finishes last was measured and dropped: the device-scope release/acquire it
-// needs writes back and invalidates the XCD's whole L2 in every block, which
-// cost far more than the extra launch.)
+// Merging in the block that finishes last was measured and dropped: the
+// device-scope release/acquire it needs writes back and invalidates the XCD's
+// whole L2 in every block, which cost far more than the extra launch.
 //
 // A K or V row is 128 bf16 = 256 bytes = 16 lanes x 16 bytes, so one wave load
 // instruction fetches four rows; the <q, k> reduction runs inside a 16-lane DPP
-// row.  Each row group works on 4 rows at a time and the loads of the next 64
-// rows are issued before the current 64 are consumed, so a block keeps up to
-// 64 KiB of rows in flight.  The work is HBM bound (about one flop per byte), so
-// there is no MFMA here.  Logits are kept in log2 units (scale * log2(e) folded
-// into q) so that exp2 is the only transcendental.
+// row.  Each row group works on 4 rows at a time; list entry, page-table entry
+// and row loads of successive iterations run as a pipeline (see the kernel), so
+// a block keeps up to 64 KiB of rows in flight.  The piece of the list a block
+// takes is rotated by the list's index, which spreads the pieces of lists of
+// different lengths over the XCDs.  The work is HBM bound (about one flop per
+// byte), so there is no MFMA here.  Logits are kept in log2 units (scale *
+// log2(e) folded into q) so that exp2 is the only transcendental.
 #include "kernels.hpp"
 
 #include <math.h>
