@@ -154,3 +154,31 @@ def test_c4_full_size_sampled_pairs_paged():
     t_lens = W.draw_lengths(np.random.Generator(np.random.PCG64(np.random.SeedSequence(W.BASE_SEED + 4004))), 64, 4096, 65536)
     longest, shortest = int(np.argmax(t_lens)), int(np.argmin(t_lens))
     run_sampled(cfg, W.BASE_SEED + 4004, [(longest, 2), (shortest, 5), (31, 0)])
+
+
+def test_topk_at_the_context_limit():
+    """SCORE + TOPK at the largest context a 32-bit context accepts (4 Mi tokens: 256 blocks of 8 units of
+    2048 tokens per sequence), uniform random codes, k = N / 32, one KV head with two query heads."""
+    import paper_2412_14468_amd as ha
+    import gpu_util as gu
+    n, k, Hq = 4 * 1024 * 1024, 131072, 2
+    rng = np.random.default_rng(W.BASE_SEED + 4096)
+    codes = rng.integers(0, 2 ** 32, size=(1, 1, n), dtype=np.uint64).astype(np.uint32)
+    q_codes = rng.integers(0, 2 ** 32, size=(1, Hq), dtype=np.uint64).astype(np.uint32)
+    kz = torch.zeros((1, 1, 4, 128), dtype=torch.bfloat16, device=DEV)       # K/V are not touched by SCORE + TOPK
+    cache = ha.KvCache(kz, kz, gu.u32_dev(codes), torch.tensor([n], dtype=torch.int32, device=DEV), n)
+    cache.c.n_max = n                                                         # the code store has n rows
+    ctx = ha.Context(Hq, 1, 1, n, k)
+    idx = torch.full((1, Hq, k), -7, dtype=torch.int32, device=DEV)
+    count = torch.zeros((1, Hq), dtype=torch.int32, device=DEV)
+    thr = torch.zeros((1, Hq), dtype=torch.uint8, device=DEV)
+    ctx.hashattn_score_topk(gu.u32_dev(q_codes), cache, 1, None, k, idx, count, thr)
+    torch.cuda.synchronize()
+    idx_h = idx.cpu().numpy()
+    for h in range(Hq):
+        sc = oracle.scores(int(q_codes[0, h]), codes[0, 0])
+        ref, rthr = oracle.topk_hist(sc, k)
+        assert int(count[0, h]) == k and int(thr[0, h]) == rthr
+        np.testing.assert_array_equal(idx_h[0, h], ref)
+    with pytest.raises(ha.HashAttnError, match="max_context"):
+        ha.Context(Hq, 1, 1, n + 1, k)
