@@ -17,6 +17,7 @@ struct hashattn_ctx {
     int32_t* blk_cum;
     int32_t blocks_pitch;
     uint4* frags;                 // bf16 weight fragments of the matrix-core key encoder, per KV head
+    int32_t* append_done;         // block counter of the decode-time append kernel (zero between calls)
     int64_t frag_bytes;
     // split partials shared by GATHER-ATT and the dense kernel
     float* part;
@@ -221,7 +222,9 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
 
     if ((e = hipMalloc(reinterpret_cast<void**>(&ctx->blk_cum), hist_bytes)) != hipSuccess ||
         (e = hipMalloc(reinterpret_cast<void**>(&ctx->part), part_bytes)) != hipSuccess ||
-        (e = hipMalloc(reinterpret_cast<void**>(&ctx->frags), ctx->frag_bytes)) != hipSuccess) {
+        (e = hipMalloc(reinterpret_cast<void**>(&ctx->frags), ctx->frag_bytes)) != hipSuccess ||
+        (e = hipMalloc(reinterpret_cast<void**>(&ctx->append_done), 256)) != hipSuccess ||
+        (e = hipMemset(ctx->append_done, 0, 256)) != hipSuccess) {
         const long long wanted = (long long)ctx->scratch_bytes;
         hashattn_destroy(ctx);
         return fail(nullptr, HASHATTN_HIP_ERROR, "create: allocating %lld scratch bytes: %s", wanted, hipGetErrorString(e));
@@ -244,6 +247,7 @@ hashattn_status hashattn_destroy(hashattn_ctx* ctx)
     if (ctx->blk_cum) (void)hipFree(ctx->blk_cum);
     if (ctx->part) (void)hipFree(ctx->part);
     if (ctx->frags) (void)hipFree(ctx->frags);
+    if (ctx->append_done) (void)hipFree(ctx->append_done);
     delete ctx;
     return HASHATTN_OK;
 }
@@ -272,7 +276,7 @@ hashattn_status hashattn_encode_keys(hashattn_ctx* ctx, const hashattn_mlp* phi_
         if ((int64_t)cache->max_seq_len + n_new > ctx->cfg.max_context)
             return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "encode_keys: append would exceed max_context %lld", (long long)ctx->cfg.max_context);
     }
-    const ha::EncodeScratch enc{ctx->frags, ha::encode_mfma_scratch_bytes_per_head() / 16};
+    const ha::EncodeScratch enc{ctx->frags, ha::encode_mfma_scratch_bytes_per_head() / 16, ctx->append_done};
     const hipError_t e = ha::launch_encode_keys(view_of(phi_kv), view_of(ctx, cache), paged,
                                                 static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
                                                 batch, n_new, cache->max_seq_len, &enc, static_cast<hipStream_t>(stream));

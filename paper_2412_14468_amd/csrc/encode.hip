@@ -120,11 +120,33 @@ __device__ __forceinline__ void store_codes(const float (*a)[kMaxWidth], int n_h
     }
 }
 
+// Append mode: the sequence lengths may only move once every block has placed its rows, and a
+// separate launch for that costs more than the encoding.  Every block counts itself in after its
+// last use of seq_lens; the block that completes the count adds n_new to every length and resets
+// the counter for the next call.  Nothing a block wrote has to be visible to another one here, only
+// the counter, which is an atomic at device scope.
+__device__ __forceinline__ void finish_append(int32_t* __restrict__ done, int32_t* __restrict__ seq_lens,
+                                              int batch, int n_new)
+{
+    __shared__ int last;
+    __syncthreads();                                   // all threads of the block have read seq_lens
+    if (threadIdx.x == 0) {
+        const int total = gridDim.x * gridDim.y;
+        const int before = atomicAdd(done, 1);
+        last = before == total - 1;
+        if (last) *done = 0;
+    }
+    __syncthreads();
+    if (last)
+        for (int b = threadIdx.x; b < batch; b += blockDim.x) seq_lens[b] += n_new;
+}
+
 // Any supported network shape; weights are fetched inside the layer loops.
 template <int MODE, bool PAGED>
 __global__ __launch_bounds__(256) void encode_vec_kernel(MlpView phi, int n_heads, const uint16_t* __restrict__ x,
                                                          const uint16_t* __restrict__ v_new, int n_vec, int n_new,
-                                                         uint32_t* __restrict__ q_codes, KvView c, int n_cap)
+                                                         uint32_t* __restrict__ q_codes, KvView c, int n_cap,
+                                                         int32_t* __restrict__ done)
 {
     __shared__ float act[2][kVecPerBlock][kMaxWidth];
     __shared__ float red[kVecPerBlock * 256];
@@ -134,6 +156,7 @@ __global__ __launch_bounds__(256) void encode_vec_kernel(MlpView phi, int n_head
     const int cur = mlp_gemv(phi, head, act, red);
     store_codes<MODE, PAGED>(act[cur], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap,
                              phi.dims[phi.n_layers] / kBits);
+    if constexpr (MODE == 1) finish_append(done, c.seq_lens, n_vec / n_new, n_new);
 }
 
 // ---- shapes known at compile time: every thread fetches all its weights of all layers up front,
@@ -185,7 +208,7 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
                                                                const uint16_t* __restrict__ x,
                                                                const uint16_t* __restrict__ v_new, int n_vec,
                                                                int n_new, uint32_t* __restrict__ q_codes,
-                                                               KvView c, int n_cap)
+                                                               KvView c, int n_cap, int32_t* __restrict__ done)
 {
     __shared__ float act[2][kVecPerBlock][kMaxWidth];
     __shared__ float red[kVecPerBlock * 256];
@@ -207,29 +230,31 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
     if constexpr (NL == 3)
         gemv_layer<I2, kBits, VT>(w2, phi.bias[2] ? phi.bias[2] + (int64_t)head * kBits : nullptr, act[0], act[1], red, true);
     store_codes<MODE, PAGED>(act[NL & 1], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+    if constexpr (MODE == 1) finish_append(done, c.seq_lens, n_vec / n_new, n_new);
 }
 
 template <int MODE, bool PAGED>
 void launch_encode_vec(const MlpView& phi, dim3 grid, int n_heads, const uint16_t* x, const uint16_t* v_new,
-                       int n_vec, int n_new, uint32_t* q_codes, const KvView& c, int n_cap, hipStream_t stream)
+                       int n_vec, int n_new, uint32_t* q_codes, const KvView& c, int n_cap, int32_t* done,
+                       hipStream_t stream)
 {
     const int nl = phi.n_layers, d1 = phi.dims[1], d2 = phi.dims[2];
     if (phi.dims[nl] != kBits)           // wider signatures: the general kernel
-        encode_vec_kernel<MODE, PAGED><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+        encode_vec_kernel<MODE, PAGED><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
     else if (nl == 1 && n_vec == 1)
-        encode_vec_fixed_kernel<MODE, PAGED, 1, 32, 32, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+        encode_vec_fixed_kernel<MODE, PAGED, 1, 32, 32, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
     else if (nl == 1)
-        encode_vec_fixed_kernel<MODE, PAGED, 1, 32, 32, kVecPerBlock><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+        encode_vec_fixed_kernel<MODE, PAGED, 1, 32, 32, kVecPerBlock><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
     else if (nl == 2 && d1 == 128 && n_vec == 1)
-        encode_vec_fixed_kernel<MODE, PAGED, 2, 128, 32, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+        encode_vec_fixed_kernel<MODE, PAGED, 2, 128, 32, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
     else if (nl == 2 && d1 == 128)
-        encode_vec_fixed_kernel<MODE, PAGED, 2, 128, 32, kVecPerBlock><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+        encode_vec_fixed_kernel<MODE, PAGED, 2, 128, 32, kVecPerBlock><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
     else if (nl == 3 && d1 == 128 && d2 == 128 && n_vec == 1)
-        encode_vec_fixed_kernel<MODE, PAGED, 3, 128, 128, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+        encode_vec_fixed_kernel<MODE, PAGED, 3, 128, 128, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
     else if (nl == 3 && d1 == 128 && d2 == 128)
-        encode_vec_fixed_kernel<MODE, PAGED, 3, 128, 128, kVecPerBlock><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+        encode_vec_fixed_kernel<MODE, PAGED, 3, 128, 128, kVecPerBlock><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
     else
-        encode_vec_kernel<MODE, PAGED><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+        encode_vec_kernel<MODE, PAGED><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
 }
 
 __global__ void bump_seq_lens_kernel(int32_t* seq_lens, int batch, int n_new)
@@ -377,7 +402,7 @@ hipError_t launch_encode_query(const MlpView& phi, const uint16_t* q, int batch,
 {
     const dim3 grid(n_heads, (batch + kVecPerBlock - 1) / kVecPerBlock);
     KvView none{};
-    launch_encode_vec<0, false>(phi, grid, n_heads, q, nullptr, batch, 1, q_codes, none, 0, stream);
+    launch_encode_vec<0, false>(phi, grid, n_heads, q, nullptr, batch, 1, q_codes, none, 0, nullptr, stream);
     return hipGetLastError();
 }
 
@@ -388,16 +413,16 @@ hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
 {
     const int H = kv.n_kv_heads;
     size_t lds_bytes = 0;
-    const bool mfma = sc && sc->frags && encode_mfma_supported(phi);    // bulk work goes to the matrix cores
+    const bool mfma = sc->frags && encode_mfma_supported(phi);          // bulk work goes to the matrix cores
     if (k_new) {
         if (n_new * batch <= 4 * kVecPerBlock) {
-            // decode-time append: one GEMV-shaped launch writes rows and codes
+            // decode-time append: one GEMV-shaped launch writes rows and codes and moves the lengths
             const int n_vec = (int)(batch * n_new);
             const dim3 grid(H, (n_vec + kVecPerBlock - 1) / kVecPerBlock);
             if (paged)
-                launch_encode_vec<1, true>(phi, grid, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len, stream);
+                launch_encode_vec<1, true>(phi, grid, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len, sc->append_done, stream);
             else
-                launch_encode_vec<1, false>(phi, grid, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len, stream);
+                launch_encode_vec<1, false>(phi, grid, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len, sc->append_done, stream);
         } else {
             const dim3 cgrid((unsigned)((n_new * 16 + 255) / 256), H, batch);
             const dim3 egrid((unsigned)((n_new + kTile - 1) / kTile), H, batch);
@@ -410,8 +435,8 @@ hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
                 if (paged) encode_bulk_kernel<true><<<egrid, 256, lds_bytes, stream>>>(phi, kv, max_seq_len, n_new, 0);
                 else encode_bulk_kernel<false><<<egrid, 256, lds_bytes, stream>>>(phi, kv, max_seq_len, n_new, 0);
             }
+            bump_seq_lens_kernel<<<(batch + 255) / 256, 256, 0, stream>>>(kv.seq_lens, batch, (int)n_new);
         }
-        bump_seq_lens_kernel<<<(batch + 255) / 256, 256, 0, stream>>>(kv.seq_lens, batch, (int)n_new);
     } else {
         const int64_t span = n_new < max_seq_len ? n_new : max_seq_len;
         if (span > 0 && mfma) {

@@ -21,13 +21,15 @@ struct TopkScratch {
 hipError_t launch_encode_query(const MlpView& phi, const uint16_t* q, int batch, int n_heads,
                                uint32_t* q_codes, hipStream_t stream);
 
-// Scratch of the matrix-core bulk encoder: bf16 weight fragments of every KV head.
+// Scratch of the key encoders: bf16 weight fragments of every KV head for the matrix-core bulk kernel
+// (frags == nullptr: vector kernels only), and the block counter of the decode-time append (zero
+// between calls).
 struct EncodeScratch {
     uint4* frags;
     int64_t quads_per_head;        // 16-byte units per head
+    int32_t* append_done;
 };
 
-// sc == nullptr (or a network shape the matrix-core kernel does not cover): vector kernels only.
 hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
                               const uint16_t* k_new, const uint16_t* v_new,
                               int batch, int64_t n_new, int max_seq_len, const EncodeScratch* sc,
