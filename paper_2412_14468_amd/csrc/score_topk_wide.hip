@@ -26,6 +26,8 @@ constexpr int kAllTies = 0x7fffffff;
 constexpr int kWpb = kTopkWavesPerBlock;
 constexpr int kThreads = kWpb * kWave;
 constexpr int kMaxSteps = 16;                 // 64-token steps per unit: units of at most 1024 tokens
+// steps whose codes are in flight ahead of the one being scored (a ring of registers)
+__host__ __device__ constexpr int depth_of(int W) { return W <= 4 ? 4 : 2; }
 
 __host__ __device__ constexpr int bins_of(int W) { return 32 * W + 1; }
 // LDS histogram copies per bin: as many as fit about 32 KiB, a power of two, at most 32
@@ -96,13 +98,29 @@ __global__ __launch_bounds__(kThreads) void score_hist_wide_kernel(KvView c, con
     __syncthreads();
 
     unsigned* mine = hist + (lane & (kCopiesW - 1));
-    for (int64_t base = t_begin; base < t_end; base += kWave) {
-        const int t = (int)base + lane;
-        if (t >= lo && t < min(t_end, hi)) {
-            const CodeWords<W> k = load_code<PAGED, W>(c, b, kvh, t);
+    const int s_end = min(t_end, hi);                               // scored tokens of this unit: [max(t_begin, lo), s_end)
+    auto fetch = [&](int t) {                                        // the code of token t, zeros outside the scored range
+        CodeWords<W> r;
 #pragma unroll
-            for (int j = 0; j < G; ++j)
-                atomicAdd(&mine[(j * kBinsW + similarity<W>(k, qs + j * W)) * kCopiesW], 1u);
+        for (int i = 0; i < W; ++i) r.w[i] = 0u;
+        if (t >= lo && t < s_end) r = load_code<PAGED, W>(c, b, kvh, t);
+        return r;
+    };
+    constexpr int kDepth = depth_of(W);
+    CodeWords<W> ring[kDepth];
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) ring[d] = fetch((int)t_begin + d * kWave + lane);
+    for (int64_t base = t_begin; base < t_end; base += kDepth * kWave) {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            const int t = (int)base + d * kWave + lane;
+            const CodeWords<W> cur = ring[d];
+            ring[d] = fetch(t + kDepth * kWave);                     // refill: kDepth steps ahead
+            if (t >= lo && t < s_end) {
+#pragma unroll
+                for (int j = 0; j < G; ++j)
+                    atomicAdd(&mine[(j * kBinsW + similarity<W>(cur, qs + j * W)) * kCopiesW], 1u);
+            }
         }
     }
     __syncthreads();
@@ -174,7 +192,13 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
         const int j = i / kRow, col = i - j * kRow;
         const int32_t* p = blk_cum + (bh0 + j) * blocks_pitch * kRow + col;
         int v = 0;
-        for (int blk = 0; blk < n_blocks; ++blk) v += p[(int64_t)blk * kRow];
+        for (int blk0 = 0; blk0 < n_blocks; blk0 += 16) {           // sixteen independent loads per trip to memory
+            int part[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) part[u] = blk0 + u < n_blocks ? p[(int64_t)(blk0 + u) * kRow] : 0;
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v += part[u];
+        }
         tot[i] = v;
     }
     __syncthreads();
@@ -221,21 +245,36 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
 #pragma unroll
     for (int j = 0; j < G; ++j) { T[j] = uniform(thr[j]); cgt[j] = ceq[j] = 0; }
     const int n_steps = active ? (t_end - (int)t_begin + kWave - 1) / kWave : 0;
-    for (int s = 0; s < n_steps; ++s) {
-        const int t = (int)t_begin + s * kWave + lane;
-        const bool valid = t < t_end, scored = valid && t >= lo && t < hi;
-        CodeWords<W> kc;
+    auto fetch = [&](int t) {                                        // the code of token t, zeros if it is not scored
+        CodeWords<W> r;
 #pragma unroll
-        for (int i = 0; i < W; ++i) kc.w[i] = 0u;
-        if (scored) kc = load_code<PAGED, W>(c, b, kvh, t);
+        for (int i = 0; i < W; ++i) r.w[i] = 0u;
+        if (t < t_end && t >= lo && t < hi) r = load_code<PAGED, W>(c, b, kvh, t);
+        return r;
+    };
+    constexpr int kDepth = depth_of(W);
+    CodeWords<W> ring[kDepth];
 #pragma unroll
-        for (int j = 0; j < G; ++j) {
-            const int sc = similarity<W>(kc, qs + j * W);
-            const uint64_t g_mask = __ballot((scored && sc > T[j]) || (valid && !scored));   // kept tokens are always taken
-            const uint64_t e_mask = __ballot(scored && sc == T[j]);
-            if (lane == 0) { m_gt[wave][s][j] = g_mask; m_eq[wave][s][j] = e_mask; }
-            cgt[j] += __popcll(g_mask);
-            ceq[j] += __popcll(e_mask);
+    for (int d = 0; d < kDepth; ++d) ring[d] = fetch((int)t_begin + d * kWave + lane);
+    for (int s0 = 0; s0 < n_steps; s0 += kDepth) {
+#pragma unroll
+        for (int d = 0; d < kDepth; ++d) {
+            const int s = s0 + d;
+            const int t = (int)t_begin + s * kWave + lane;
+            const CodeWords<W> kc = ring[d];
+            ring[d] = fetch(t + kDepth * kWave);                     // refill: kDepth steps ahead
+            if (s < n_steps) {                                       // uniform over the wave
+                const bool valid = t < t_end, scored = valid && t >= lo && t < hi;
+#pragma unroll
+                for (int j = 0; j < G; ++j) {
+                    const int sc = similarity<W>(kc, qs + j * W);
+                    const uint64_t g_mask = __ballot((scored && sc > T[j]) || (valid && !scored));   // kept tokens are always taken
+                    const uint64_t e_mask = __ballot(scored && sc == T[j]);
+                    if (lane == 0) { m_gt[wave][s][j] = g_mask; m_eq[wave][s][j] = e_mask; }
+                    cgt[j] += __popcll(g_mask);
+                    ceq[j] += __popcll(e_mask);
+                }
+            }
         }
     }
     if (lane == 0) {
