@@ -127,16 +127,31 @@ ha::KvView view_of(const hashattn_ctx* ctx, const hashattn_kv* kv)
 // keep the number of blocks (and of per-block tables every block has to sum) down at long contexts.
 // `mixed`: the caller gave a k per sequence, so lengths differ; a block is sized by the longest
 // sequence and mostly idle for a short one, hence the smaller cap.
-int pick_unit_tokens(const hashattn_ctx* ctx, int batch, int max_seq_len, bool mixed)
+int pick_unit_tokens(const hashattn_ctx* ctx, int batch, int max_seq_len, bool mixed, int* waves_per_block)
 {
     const int64_t lanes = (int64_t)batch * ctx->cfg.n_kv_heads;
-    const int cap = (mixed || ctx->cfg.bits > 32) ? kMaxUnit / 2 : kMaxUnit;      // wide codes: units of at most 1024
-    int unit = kMinUnit;
-    auto blocks = [&](int u) { return (max_seq_len + (int64_t)u * ha::kTopkWavesPerBlock - 1) / ((int64_t)u * ha::kTopkWavesPerBlock); };
-    // two 8-wave blocks share a CU; up to about one block per CU keeps the per-block tables short
-    while (unit < cap && lanes * blocks(unit) > 256) unit *= 2;
-    // never more blocks per sequence than the scratch pitch
-    while (unit < (ctx->cfg.bits > 32 ? kMaxUnit / 2 : kMaxUnit) && blocks(unit) > ctx->blocks_pitch) unit *= 2;
+    const bool wide = ctx->cfg.bits > 32;
+    const int cap = (mixed || wide) ? kMaxUnit / 2 : kMaxUnit;      // wide codes: units of at most 1024
+    const int hard_cap = wide ? kMaxUnit / 2 : kMaxUnit;
+    auto pick = [&](int wpb) {
+        auto blocks = [&](int u) { return (max_seq_len + (int64_t)u * wpb - 1) / ((int64_t)u * wpb); };
+        int unit = kMinUnit;
+        // up to about one block per CU keeps the per-block tables short
+        while (unit < cap && lanes * blocks(unit) > 256) unit *= 2;
+        // never more blocks per sequence than the scratch pitch
+        while (unit < hard_cap && blocks(unit) > ctx->blocks_pitch) unit *= 2;
+        return unit;
+    };
+    // Blocks of 8 waves: two share a CU and one's table prologue overlaps the other's scoring.  With few
+    // (sequence, KV head) pairs and a very long context that would mean units of 2048 tokens (two chunks
+    // per wave in the select); blocks of 16 waves with units of 1024 measured faster there.
+    int wpb = ha::kTopkWavesPerBlock;
+    int unit = pick(wpb);
+    if (!wide && !mixed && lanes <= 16 && unit == kMaxUnit) {
+        wpb = 16;
+        unit = pick(wpb);
+    }
+    *waves_per_block = wpb;
     return unit;
 }
 
@@ -315,9 +330,10 @@ hashattn_status hashattn_score_topk_window(hashattn_ctx* ctx, const uint32_t* q_
         return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "score_topk: k_max + n_sink + n_local = %lld exceeds max_k %lld",
                     (long long)k_max + n_sink + n_local, (long long)ctx->cfg.max_k);
     const ha::TopkScratch sc{ctx->blk_cum, ctx->blocks_pitch};
-    const int unit = pick_unit_tokens(ctx, batch, cache->max_seq_len, k_per_seq != nullptr);
+    int wpb = 0;
+    const int unit = pick_unit_tokens(ctx, batch, cache->max_seq_len, k_per_seq != nullptr, &wpb);
     const ha::TopkCall call{q_codes, k_per_seq, k_max, n_sink, n_local, batch, ctx->cfg.n_q_heads, cache->max_seq_len,
-                            idx, count, threshold};
+                            wpb, idx, count, threshold};
     const hipError_t e = ctx->cfg.bits == ha::kBits
         ? ha::launch_score_topk(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group, call, unit, sc,
                                 static_cast<hipStream_t>(stream))

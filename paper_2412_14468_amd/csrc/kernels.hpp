@@ -52,6 +52,7 @@ struct TopkCall {
     const int32_t* k_per_seq;
     int32_t k_max, n_sink, n_local;
     int32_t batch, n_q_heads, max_seq_len;
+    int32_t waves_per_block;      // 8 or 16 units per block (32-bit signatures; wider ones always use 8)
     int32_t* idx;
     int32_t* count;
     uint8_t* threshold;

@@ -3,7 +3,7 @@
 // The score of a token is the Hamming similarity 32 - popcount(q_code ^ k_code),
 // an integer in 0..32, so top-k is a 33-bin counting select in two launches.
 // A sequence is cut into "units" (contiguous runs of tokens, one per wave); a block
-// of 8 waves owns 8 consecutive units of one KV head and serves the G query heads
+// of 8 (or 16) waves owns as many consecutive units of one KV head and serves the G query heads
 // of its group from one read of the codes.
 //   1. score_hist   every wave scores its unit for the G heads and counts scores per
 //                   head in one LDS histogram per block.  A bin has 32 copies, picked
@@ -37,8 +37,6 @@ namespace {
 constexpr int kAllTies = 0x7fffffff;
 constexpr int kBinCopies = 32;        // LDS copies of a histogram bin, one per bank
 constexpr int kChunk = 4 * 4 * kWave; // most tokens a wave handles at once: four 16-byte loads per lane
-constexpr int kWpb = kTopkWavesPerBlock;
-constexpr int kThreads = kWpb * kWave;
 
 // NIT 16-byte loads per lane, coalesced: load `it` of lane L holds tokens base + it * 256 + 4 L .. + 3.
 // Needs base < t_end.  Pieces past t_end repeat the last piece before it instead of being skipped
@@ -79,8 +77,9 @@ __device__ __forceinline__ void count_chunk(const uint4 (&cw)[4], int base, int 
 // Table written by score_hist and read by topk_select; a row holds #{score >= s} for s = 0..32 and
 // a zero in slot 33, so that "row[T + 1]" is valid for T = 32:
 //   blk_cum:  [B][Hq][blocks_pitch][34] ints, one row per block of 8 units
-template <int G, bool PAGED>
-__global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const uint32_t* __restrict__ q_codes,
+// WPB: waves (units) per block, 8 or 16.
+template <int G, bool PAGED, int WPB>
+__global__ __launch_bounds__(WPB * kWave) void score_hist_kernel(KvView c, const uint32_t* __restrict__ q_codes,
                                                               int n_q_heads, int n_cap, int unit_tokens,
                                                               int n_sink, int n_local,
                                                               int blocks_pitch, int32_t* __restrict__ blk_cum)
@@ -90,7 +89,7 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
     const int tid = threadIdx.x, wave = uniform(tid >> 6), lane = tid & 63;    // wave: scalar, so are the token ranges
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int bx = rotated_block(blockIdx.x, kvh + b, gridDim.x);      // block index inside the sequence
-    const int unit = bx * kWpb + wave;
+    const int unit = bx * WPB + wave;
     const int64_t t_begin = (int64_t)unit * unit_tokens;
     // loads complete in issue order: the few small ones go first, so that waiting for them does not
     // mean waiting for the codes
@@ -107,7 +106,7 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
         if (t_begin < n_cap) load_chunk<PAGED, 4>(c, b, kvh, (int)t_begin, (int)min((int64_t)n_cap, t_begin + unit_tokens), lane, cw);
     }
     const int n = min(n_raw, n_cap);           // n_cap: the host's bound that sized grid and scratch
-    if ((int64_t)bx * kWpb * unit_tokens >= n) return;      // whole block beyond the sequence
+    if ((int64_t)bx * WPB * unit_tokens >= n) return;      // whole block beyond the sequence
     const bool active = t_begin < n;
     const int t_end = (int)min((int64_t)n, t_begin + unit_tokens);
     const int lo = min(n_sink, n), hi = max(lo, n - n_local);   // always-kept tokens [0, lo) and [hi, n) are not scored
@@ -117,7 +116,7 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
     uint32_t qc[G];
 #pragma unroll
     for (int j = 0; j < G; ++j) qc[j] = (uint32_t)uniform(qraw[j]);
-    for (int i = tid; i < G * kBins * kBinCopies; i += kThreads) hist[i] = 0u;
+    for (int i = tid; i < G * kBins * kBinCopies; i += (WPB * kWave)) hist[i] = 0u;
     __syncthreads();
 
     if (active) {
@@ -136,7 +135,7 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
     }
     __syncthreads();
     // the 32 copies of a bin: four threads add eight each, then across the quad
-    for (int row = tid >> 2; row < G * kBins; row += kThreads / 4) {
+    for (int row = tid >> 2; row < G * kBins; row += (WPB * kWave) / 4) {
         const uint4* p = reinterpret_cast<const uint4*>(hist + row * kBinCopies + (tid & 3) * 8);
         const uint4 a = p[0], d = p[1];
         int s = (int)((a.x + a.y) + (a.z + a.w) + (d.x + d.y) + (d.z + d.w));
@@ -146,7 +145,7 @@ __global__ __launch_bounds__(kThreads) void score_hist_kernel(KvView c, const ui
     }
     __syncthreads();
     // cumulative counts per head by a wave scan (lanes 0..32 hold the bins, lane 33 the zero slot)
-    for (int j = wave; j < G; j += kWpb) {
+    for (int j = wave; j < G; j += WPB) {
         const int h = lane < kBins ? bsum[j * kBins + lane] : 0;
         const int incl = wave_incl_scan_i32(h);
         const int total = __builtin_amdgcn_readlane(incl, 63);
@@ -241,8 +240,8 @@ __device__ __forceinline__ void emit_ids(unsigned m, int rank, int t0, int pitch
 
 // NIT: 16-byte loads per lane and chunk (unit_tokens = 256 NIT for NIT < 4); NCH: chunks of 1024
 // tokens per unit (unit_tokens = 1024 NCH, NIT = 4).
-template <int G, bool PAGED, int NIT, int NCH>
-__global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const uint32_t* __restrict__ q_codes,
+template <int G, bool PAGED, int NIT, int NCH, int WPB>
+__global__ __launch_bounds__(WPB * kWave) void topk_select_kernel(KvView c, const uint32_t* __restrict__ q_codes,
                                                                const int32_t* __restrict__ k_per_seq, int k_max,
                                                                int n_sink, int n_local, int pitch,
                                                                int n_q_heads, int n_cap, int blocks_pitch,
@@ -253,13 +252,13 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
     constexpr int kTpl = 4 * NIT;                              // tokens per lane and chunk
     constexpr int kChunkTokens = kTpl * kWave;
     constexpr int kUnitTokens = kChunkTokens * NCH;
-    constexpr int kBlockTokens = kUnitTokens * kWpb;
-    constexpr int kRowsPerPass = kThreads / kCumRow;           // 30 table rows are read side by side
+    constexpr int kBlockTokens = kUnitTokens * WPB;
+    constexpr int kRowsPerPass = (WPB * kWave) / kCumRow;           // 30 table rows are read side by side
     constexpr int kPairs = (G + 1) / 2;                        // two heads share a packed wave sum / scan
     extern __shared__ uint4 stage_all[];                       // NIT > 1: 64 * NIT slots per wave
     __shared__ int tot[G * kCumRow];
     __shared__ int thr[G], posb[G], quotab[G];                 // per head: T, first output slot and tie quota of the block
-    __shared__ int wcnt[kWpb][kPairs], weq[kWpb][kPairs];      // per wave: selected / tied tokens, two heads per int
+    __shared__ int wcnt[WPB][kPairs], weq[WPB][kPairs];      // per wave: selected / tied tokens, two heads per int
     const int tid = threadIdx.x, wave = uniform(tid >> 6), lane = tid & 63;    // wave: scalar, so are the token ranges
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int bx = rotated_block(blockIdx.x, kvh + b, gridDim.x);      // block index inside the sequence
@@ -285,7 +284,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
 #pragma unroll
     for (int j = 0; j < G; ++j) qraw[j] = (int)q_codes[bh0 + j];
     // the codes go last: loads complete in issue order, and nothing before the scoring needs them
-    const int64_t t_begin = ((int64_t)bx * kWpb + wave) * kUnitTokens;
+    const int64_t t_begin = ((int64_t)bx * WPB + wave) * kUnitTokens;
     uint4 cw[NIT];
 #pragma unroll
     for (int it = 0; it < NIT; ++it) cw[it] = make_uint4(0u, 0u, 0u, 0u);   // element by element: keeps the array in registers
@@ -295,7 +294,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
     uint32_t qc[G];
 #pragma unroll
     for (int j = 0; j < G; ++j) qc[j] = (uint32_t)uniform(qraw[j]);
-    for (int i = tid; i < G * kCumRow; i += kThreads) tot[i] = 0;
+    for (int i = tid; i < G * kCumRow; i += (WPB * kWave)) tot[i] = 0;
 
     const int n = min(n_raw, n_cap);
     // the first `lo` and the tokens from `hi` on are always taken; k counts the tokens retrieved in between
@@ -328,7 +327,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
     __syncthreads();
 
     // ---- selection parameters: wave j works them out for head j
-    for (int j = wave; j < G; j += kWpb) {
+    for (int j = wave; j < G; j += WPB) {
         const int64_t bh = bh0 + j;
         const int32_t* tab = blk_cum + bh * blocks_pitch * kCumRow;
         const int cum = lane < kCumRow ? tot[j * kCumRow + lane] : 0;   // #{score >= lane} over the sequence
@@ -471,31 +470,50 @@ __global__ __launch_bounds__(kThreads) void topk_select_kernel(KvView c, const u
     }
 }
 
-template <int G, bool PAGED, int NIT, int NCH>
+template <int G, bool PAGED, int NIT, int NCH, int WPB>
 hipError_t select_variant(bool setup_only, const KvView& kv, const TopkCall& a, const TopkScratch& sc, dim3 grid,
                           hipStream_t stream)
 {
-    constexpr int lds = NIT > 1 ? kWpb * kWave * NIT * (int)sizeof(uint4) : 0;
+    constexpr int lds = NIT > 1 ? WPB * kWave * NIT * (int)sizeof(uint4) : 0;
     if (setup_only)
-        return hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_select_kernel<G, PAGED, NIT, NCH>),
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_select_kernel<G, PAGED, NIT, NCH, WPB>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds);
-    topk_select_kernel<G, PAGED, NIT, NCH><<<grid, dim3(kThreads), lds, stream>>>(
+    topk_select_kernel<G, PAGED, NIT, NCH, WPB><<<grid, dim3(WPB * kWave), lds, stream>>>(
         kv, a.q_codes, a.k_per_seq, a.k_max, a.n_sink, a.n_local, a.k_max + a.n_sink + a.n_local, a.n_q_heads,
         a.max_seq_len, sc.blocks_pitch, sc.blk_cum, a.idx, a.count, a.threshold);
     return hipSuccess;
 }
 
-template <int G, bool PAGED>
+template <int G, bool PAGED, int WPB>
 hipError_t select_by_unit(bool setup_only, int unit_tokens, const KvView& kv, const TopkCall& a, const TopkScratch& sc,
                           dim3 grid, hipStream_t stream)
 {
     switch (unit_tokens) {
-    case 256: return select_variant<G, PAGED, 1, 1>(setup_only, kv, a, sc, grid, stream);
-    case 512: return select_variant<G, PAGED, 2, 1>(setup_only, kv, a, sc, grid, stream);
-    case 1024: return select_variant<G, PAGED, 4, 1>(setup_only, kv, a, sc, grid, stream);
-    case 2048: return select_variant<G, PAGED, 4, 2>(setup_only, kv, a, sc, grid, stream);
+    case 256: return select_variant<G, PAGED, 1, 1, WPB>(setup_only, kv, a, sc, grid, stream);
+    case 512: return select_variant<G, PAGED, 2, 1, WPB>(setup_only, kv, a, sc, grid, stream);
+    case 1024: return select_variant<G, PAGED, 4, 1, WPB>(setup_only, kv, a, sc, grid, stream);
+    case 2048: return select_variant<G, PAGED, 4, 2, WPB>(setup_only, kv, a, sc, grid, stream);
     default: return hipErrorInvalidValue;
     }
+}
+
+template <int G, bool PAGED, int WPB>
+hipError_t launch_gpw(bool setup_only, const KvView& kv, const TopkCall& a, int unit_tokens, const TopkScratch& sc,
+                      hipStream_t stream)
+{
+    if (setup_only) {
+        for (int unit = 256; unit <= 2048; unit *= 2)
+            if (hipError_t e = select_by_unit<G, PAGED, WPB>(true, unit, kv, a, sc, dim3(1), stream); e != hipSuccess) return e;
+        return hipSuccess;
+    }
+    const int64_t block_tokens = (int64_t)WPB * unit_tokens;
+    int n_blocks = (int)((a.max_seq_len + block_tokens - 1) / block_tokens);
+    if (n_blocks < 1) n_blocks = 1;               // block 0 of every group still reports count = 0
+    const dim3 grid(n_blocks, kv.n_kv_heads, a.batch), block(WPB * kWave);
+    score_hist_kernel<G, PAGED, WPB><<<grid, block, 0, stream>>>(kv, a.q_codes, a.n_q_heads, a.max_seq_len, unit_tokens,
+                                                             a.n_sink, a.n_local, sc.blocks_pitch, sc.blk_cum);
+    if (hipError_t e = select_by_unit<G, PAGED, WPB>(false, unit_tokens, kv, a, sc, grid, stream); e != hipSuccess) return e;
+    return hipGetLastError();
 }
 
 template <int G, bool PAGED>
@@ -503,18 +521,11 @@ hipError_t launch_gp(bool setup_only, const KvView& kv, const TopkCall& a, int u
                      hipStream_t stream)
 {
     if (setup_only) {
-        for (int unit = 256; unit <= 2048; unit *= 2)
-            if (hipError_t e = select_by_unit<G, PAGED>(true, unit, kv, a, sc, dim3(1), stream); e != hipSuccess) return e;
-        return hipSuccess;
+        if (hipError_t e = launch_gpw<G, PAGED, 8>(true, kv, a, unit_tokens, sc, stream); e != hipSuccess) return e;
+        return launch_gpw<G, PAGED, 16>(true, kv, a, unit_tokens, sc, stream);
     }
-    const int64_t block_tokens = (int64_t)kWpb * unit_tokens;
-    int n_blocks = (int)((a.max_seq_len + block_tokens - 1) / block_tokens);
-    if (n_blocks < 1) n_blocks = 1;               // block 0 of every group still reports count = 0
-    const dim3 grid(n_blocks, kv.n_kv_heads, a.batch), block(kThreads);
-    score_hist_kernel<G, PAGED><<<grid, block, 0, stream>>>(kv, a.q_codes, a.n_q_heads, a.max_seq_len, unit_tokens,
-                                                             a.n_sink, a.n_local, sc.blocks_pitch, sc.blk_cum);
-    if (hipError_t e = select_by_unit<G, PAGED>(false, unit_tokens, kv, a, sc, grid, stream); e != hipSuccess) return e;
-    return hipGetLastError();
+    return a.waves_per_block == 16 ? launch_gpw<G, PAGED, 16>(false, kv, a, unit_tokens, sc, stream)
+                                   : launch_gpw<G, PAGED, 8>(false, kv, a, unit_tokens, sc, stream);
 }
 
 template <int G>
