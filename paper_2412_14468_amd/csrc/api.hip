@@ -239,7 +239,8 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
         (e = hipMalloc(reinterpret_cast<void**>(&ctx->part), part_bytes)) != hipSuccess ||
         (e = hipMalloc(reinterpret_cast<void**>(&ctx->frags), ctx->frag_bytes)) != hipSuccess ||
         (e = hipMalloc(reinterpret_cast<void**>(&ctx->append_done), 256)) != hipSuccess ||
-        (e = hipMemset(ctx->append_done, 0, 256)) != hipSuccess) {
+        (e = hipMemset(ctx->append_done, 0, 256)) != hipSuccess ||
+        (e = hipDeviceSynchronize()) != hipSuccess) {      // the counter is zero before any stream uses it
         const long long wanted = (long long)ctx->scratch_bytes;
         hashattn_destroy(ctx);
         return fail(nullptr, HASHATTN_HIP_ERROR, "create: allocating %lld scratch bytes: %s", wanted, hipGetErrorString(e));
