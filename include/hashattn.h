@@ -35,10 +35,9 @@
  *     a code is W consecutive uint32 (codes hold W words per row, q_codes
  *     [batch][n_q_heads][W]); output unit j of the mapping is bit j % 32 of
  *     word j / 32; the score of a token is b - bitcount(xor), 0..b; the
- *     mapping networks end in b outputs.  hashattn_encode_* produce up to 256
- *     bits (512-bit codes must be supplied by the caller); `threshold` is
- *     stored as min(T, 255); max_context is at most 2 Mi tokens.  Everything
- *     else reads as for 32 bits.
+ *     mapping networks end in b outputs (hidden layers stay within 256
+ *     units); `threshold` is stored as min(T, 255); max_context is at most
+ *     2 Mi tokens.  Everything else reads as for 32 bits.
  */
 #ifndef HASHATTN_H
 #define HASHATTN_H

@@ -57,8 +57,6 @@ hashattn_status check_mlp(hashattn_ctx* ctx, const hashattn_mlp* m, int n_heads,
         return fail(ctx, HASHATTN_UNSUPPORTED, "%s: n_layers %d not in 1..3", what, m->n_layers);
     if (m->dims[0] != ha::kHeadDim || m->dims[m->n_layers] != ctx->cfg.bits)
         return fail(ctx, HASHATTN_UNSUPPORTED, "%s: network must map 128 inputs to %d outputs (the context's bits)", what, ctx->cfg.bits);
-    if (ctx->cfg.bits > 256)
-        return fail(ctx, HASHATTN_UNSUPPORTED, "%s: the mapping kernels produce at most 256 bits (SCORE/TOPK take up to 512)", what);
     for (int l = 1; l < m->n_layers; ++l)
         if (!pow2_width(m->dims[l]))
             return fail(ctx, HASHATTN_UNSUPPORTED, "%s: hidden width %d not in {32,64,128,256}", what, m->dims[l]);

@@ -18,7 +18,8 @@ namespace ha {
 
 namespace {
 
-constexpr int kMaxWidth = 256;
+constexpr int kMaxWidth = 512;        // widest layer of the general vector kernel (the last one: up to 512 bits)
+constexpr int kFixedWidth = 256;      // activation pitch of the kernels with compile-time shapes
 constexpr int kVecPerBlock = 8;
 constexpr int kTile = 64;
 
@@ -26,38 +27,40 @@ __device__ __forceinline__ float silu(float z) { return z / (1.f + expf(-z)); }
 
 // ---------------------------------------------------------------- encode_vec
 // act: [2][kVecPerBlock][kMaxWidth] floats; r: kVecPerBlock * 256 floats of partial sums, indexed
-// [part][vec][j] with parts * dout = 256.  On return act[cur] holds the pre-sign activations of the
-// last layer; returns cur.
+// [part][vec][j] with parts * cols = 256, cols = min(dout, 256) columns per pass (a 512-wide layer takes
+// two passes).  On return act[cur] holds the pre-sign activations of the last layer; returns cur.
 __device__ int mlp_gemv(const MlpView& phi, int head, float (*act)[kVecPerBlock][kMaxWidth], float* r)
 {
     const int tid = threadIdx.x;
     int cur = 0;
     for (int l = 0; l < phi.n_layers; ++l) {
         const int di = phi.dims[l], dout = phi.dims[l + 1];
-        const int parts = 256 / dout;
-        const int j = tid % dout, p = tid / dout;
+        const int cols = min(dout, 256), parts = 256 / cols;
+        const int j = tid % cols, p = tid / cols;
         const int span = di / parts;
         const float* W = phi.W[l] + (int64_t)head * di * dout;
-        float acc[kVecPerBlock];
-#pragma unroll
-        for (int v = 0; v < kVecPerBlock; ++v) acc[v] = 0.f;
-        for (int i = p * span; i < (p + 1) * span; ++i) {
-            const float w = W[(int64_t)i * dout + j];
-#pragma unroll
-            for (int v = 0; v < kVecPerBlock; ++v) acc[v] = fmaf(act[cur][v][i], w, acc[v]);
-        }
-#pragma unroll
-        for (int v = 0; v < kVecPerBlock; ++v) r[(p * kVecPerBlock + v) * dout + j] = acc[v];
-        __syncthreads();
         const bool last = (l + 1 == phi.n_layers);
-        for (int o = tid; o < kVecPerBlock * dout; o += 256) {
-            const int v = o / dout, jj = o - v * dout;
-            float z = 0.f;
-            for (int pp = 0; pp < parts; ++pp) z += r[(pp * kVecPerBlock + v) * dout + jj];
-            if (phi.bias[l]) z += phi.bias[l][(int64_t)head * dout + jj];
-            act[cur ^ 1][v][jj] = last ? z : silu(z);
+        for (int j0 = 0; j0 < dout; j0 += 256) {
+            float acc[kVecPerBlock];
+#pragma unroll
+            for (int v = 0; v < kVecPerBlock; ++v) acc[v] = 0.f;
+            for (int i = p * span; i < (p + 1) * span; ++i) {
+                const float w = W[(int64_t)i * dout + j0 + j];
+#pragma unroll
+                for (int v = 0; v < kVecPerBlock; ++v) acc[v] = fmaf(act[cur][v][i], w, acc[v]);
+            }
+#pragma unroll
+            for (int v = 0; v < kVecPerBlock; ++v) r[(p * kVecPerBlock + v) * cols + j] = acc[v];
+            __syncthreads();
+            for (int o = tid; o < kVecPerBlock * cols; o += 256) {
+                const int v = o / cols, jj = o - v * cols;
+                float z = 0.f;
+                for (int pp = 0; pp < parts; ++pp) z += r[(pp * kVecPerBlock + v) * cols + jj];
+                if (phi.bias[l]) z += phi.bias[l][(int64_t)head * dout + j0 + jj];
+                act[cur ^ 1][v][j0 + jj] = last ? z : silu(z);
+            }
+            __syncthreads();
         }
-        __syncthreads();
         cur ^= 1;
     }
     return cur;
@@ -66,8 +69,8 @@ __device__ int mlp_gemv(const MlpView& phi, int head, float (*act)[kVecPerBlock]
 // MODE 0: queries.  x = q [B][H][128]; codes -> q_codes [B][H]; vector index = b.
 // MODE 1: appended keys.  x = k_new [B][H][n_new][128]; vector index = b * n_new + j; the K and V rows
 //         are copied to cache position seq_lens[b] + j and the code stored there.
-template <int MODE>
-__device__ __forceinline__ void load_vectors(float (*act0)[kMaxWidth], int n_heads, int head, int v0,
+template <int MODE, int WD>
+__device__ __forceinline__ void load_vectors(float (*act0)[WD], int n_heads, int head, int v0,
                                              const uint16_t* __restrict__ x, int n_vec, int n_new)
 {
     const int tid = threadIdx.x;
@@ -84,9 +87,9 @@ __device__ __forceinline__ void load_vectors(float (*act0)[kMaxWidth], int n_hea
     }
 }
 
-// a: [kVecPerBlock][kMaxWidth] pre-sign activations of the last layer
-template <int MODE, bool PAGED>
-__device__ __forceinline__ void store_codes(const float (*a)[kMaxWidth], int n_heads, int head, int v0,
+// a: [kVecPerBlock][WD] pre-sign activations of the last layer
+template <int MODE, bool PAGED, int WD>
+__device__ __forceinline__ void store_codes(const float (*a)[WD], int n_heads, int head, int v0,
                                             const uint16_t* __restrict__ x, const uint16_t* __restrict__ v_new,
                                             int n_vec, int n_new, uint32_t* __restrict__ q_codes,
                                             const KvView& c, int n_cap, int words = 1)
@@ -151,10 +154,10 @@ __global__ __launch_bounds__(256) void encode_vec_kernel(MlpView phi, int n_head
     __shared__ float act[2][kVecPerBlock][kMaxWidth];
     __shared__ float red[kVecPerBlock * 256];
     const int head = blockIdx.x, v0 = blockIdx.y * kVecPerBlock;
-    load_vectors<MODE>(act[0], n_heads, head, v0, x, n_vec, n_new);
+    load_vectors<MODE, kMaxWidth>(act[0], n_heads, head, v0, x, n_vec, n_new);
     __syncthreads();
     const int cur = mlp_gemv(phi, head, act, red);
-    store_codes<MODE, PAGED>(act[cur], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap,
+    store_codes<MODE, PAGED, kMaxWidth>(act[cur], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap,
                              phi.dims[phi.n_layers] / kBits);
     if constexpr (MODE == 1) finish_append(done, c.seq_lens, n_vec / n_new, n_new);
 }
@@ -174,7 +177,7 @@ __device__ __forceinline__ void fetch_weights(const float* __restrict__ W, float
 // VT: vectors of the block that are worked on (slots VT.. of `in` and `out` are left alone)
 template <int DI, int DOUT, int VT>
 __device__ __forceinline__ void gemv_layer(const float (&w)[DI * DOUT / 256], const float* __restrict__ bias,
-                                           const float (*in)[kMaxWidth], float (*out)[kMaxWidth], float* red,
+                                           const float (*in)[kFixedWidth], float (*out)[kFixedWidth], float* red,
                                            bool last)
 {
     constexpr int SPAN = DI * DOUT / 256, PARTS = 256 / DOUT;
@@ -210,7 +213,7 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
                                                                int n_new, uint32_t* __restrict__ q_codes,
                                                                KvView c, int n_cap, int32_t* __restrict__ done)
 {
-    __shared__ float act[2][kVecPerBlock][kMaxWidth];
+    __shared__ float act[2][kVecPerBlock][kFixedWidth];
     __shared__ float red[kVecPerBlock * 256];
     const int head = blockIdx.x, v0 = blockIdx.y * kVecPerBlock;
     constexpr int O0 = NL == 1 ? kBits : D1;            // outputs of layer 0
@@ -222,14 +225,14 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
     fetch_weights<kHeadDim, O0>(phi.W[0] + (int64_t)head * kHeadDim * O0, w0);
     if constexpr (NL >= 2) fetch_weights<I1, O1>(phi.W[1] + (int64_t)head * I1 * O1, w1);
     if constexpr (NL == 3) fetch_weights<I2, kBits>(phi.W[2] + (int64_t)head * I2 * kBits, w2);
-    load_vectors<MODE>(act[0], n_heads, head, v0, x, n_vec, n_new);
+    load_vectors<MODE, kFixedWidth>(act[0], n_heads, head, v0, x, n_vec, n_new);
     __syncthreads();
     gemv_layer<kHeadDim, O0, VT>(w0, phi.bias[0] ? phi.bias[0] + (int64_t)head * O0 : nullptr, act[0], act[1], red, NL == 1);
     if constexpr (NL >= 2)
         gemv_layer<I1, O1, VT>(w1, phi.bias[1] ? phi.bias[1] + (int64_t)head * O1 : nullptr, act[1], act[0], red, NL == 2);
     if constexpr (NL == 3)
         gemv_layer<I2, kBits, VT>(w2, phi.bias[2] ? phi.bias[2] + (int64_t)head * kBits : nullptr, act[0], act[1], red, true);
-    store_codes<MODE, PAGED>(act[NL & 1], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+    store_codes<MODE, PAGED, kFixedWidth>(act[NL & 1], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap);
     if constexpr (MODE == 1) finish_append(done, c.seq_lens, n_vec / n_new, n_new);
 }
 
@@ -264,7 +267,9 @@ __global__ void bump_seq_lens_kernel(int32_t* seq_lens, int batch, int n_new)
 }
 
 // ---------------------------------------------------------------- encode_bulk
-// One layer on a 64-token tile: out[t][o] = sum_i in[t][i] W[i][o] (+bias), SiLU unless last.
+// One layer on a 64-token tile: out[t][o] = sum_i in[t][i] W[i][o] (+bias), then SiLU; the last layer
+// keeps only the signs: byte tx of token t's code, at ((uint8_t*)out)[t * DOUT / 8 + tx], has bit e set
+// when output tx*8 + e is positive (output 32 w + j is bit j of word w, least significant byte first).
 // Thread (ty, tx): outputs tx*8 .. tx*8+7 of tokens ty + rows*r, r < R.
 template <int DOUT>
 __device__ __forceinline__ void bulk_layer(const float* __restrict__ W, const float* __restrict__ bias, int di,
@@ -289,13 +294,17 @@ __device__ __forceinline__ void bulk_layer(const float* __restrict__ W, const fl
         }
     }
 #pragma unroll
-    for (int r = 0; r < R; ++r)
+    for (int r = 0; r < R; ++r) {
+        uint32_t byte = 0u;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             float z = acc[r][e];
             if (bias) z += bias[tx * 8 + e];
-            out[(ty + ROWS * r) * out_pitch + tx * 8 + e] = last ? z : silu(z);
+            if (last) byte |= (z > 0.f ? 1u : 0u) << e;
+            else out[(ty + ROWS * r) * out_pitch + tx * 8 + e] = silu(z);
         }
+        if (last) reinterpret_cast<uint8_t*>(out)[(ty + ROWS * r) * NOT + tx] = (uint8_t)byte;
+    }
 }
 
 __device__ __forceinline__ void bulk_layer_any(int dout, const float* W, const float* bias, int di,
@@ -305,7 +314,8 @@ __device__ __forceinline__ void bulk_layer_any(int dout, const float* W, const f
     case 32:  bulk_layer<32>(W, bias, di, in, in_pitch, out, out_pitch, last); break;
     case 64:  bulk_layer<64>(W, bias, di, in, in_pitch, out, out_pitch, last); break;
     case 128: bulk_layer<128>(W, bias, di, in, in_pitch, out, out_pitch, last); break;
-    default:  bulk_layer<256>(W, bias, di, in, in_pitch, out, out_pitch, last); break;
+    case 256: bulk_layer<256>(W, bias, di, in, in_pitch, out, out_pitch, last); break;
+    default:  bulk_layer<512>(W, bias, di, in, in_pitch, out, out_pitch, last); break;   // last layer only
     }
 }
 
@@ -316,8 +326,8 @@ template <bool PAGED>
 __global__ __launch_bounds__(256) void encode_bulk_kernel(MlpView phi, KvView c, int n_cap, int64_t n_new, int from_end)
 {
     extern __shared__ float lds[];                         // 2 x kTile x P floats
-    int widest = phi.dims[0];
-    for (int l = 1; l <= phi.n_layers; ++l) widest = max(widest, phi.dims[l]);
+    int widest = phi.dims[0];                              // of the layers' inputs: the last layer leaves code bytes
+    for (int l = 1; l < phi.n_layers; ++l) widest = max(widest, phi.dims[l]);
     const int P = widest + 1;                              // LDS pitch, odd to spread banks
     float* bufA = lds;
     float* bufB = lds + kTile * P;
@@ -357,12 +367,10 @@ __global__ __launch_bounds__(256) void encode_bulk_kernel(MlpView phi, KvView c,
         float* t = in; in = out; out = t;
     }
     const int words = phi.dims[phi.n_layers] / kBits;          // unit 32 w + j -> bit j of word w
+    const uint32_t* packed = reinterpret_cast<const uint32_t*>(in);     // [kTile][words], written by the last layer
     for (int o = tid; o < n_tok * words; o += 256) {
         const int t = o / words, w = o - t * words;
-        uint32_t code = 0u;
-#pragma unroll
-        for (int j = 0; j < kBits; ++j) code |= (in[t * P + 32 * w + j] > 0.f ? 1u : 0u) << j;
-        c.codes[row_of<PAGED>(c, b, head, (int)(start + t0 + t)) * words + w] = code;
+        c.codes[row_of<PAGED>(c, b, head, (int)(start + t0 + t)) * words + w] = packed[o];
     }
 }
 
@@ -388,7 +396,7 @@ __global__ __launch_bounds__(256) void append_rows_kernel(KvView c, const uint16
 hipError_t bulk_lds_setup(const MlpView& phi, bool paged, size_t* bytes)
 {
     int widest = phi.dims[0];
-    for (int l = 1; l <= phi.n_layers; ++l) widest = widest > phi.dims[l] ? widest : phi.dims[l];
+    for (int l = 1; l < phi.n_layers; ++l) widest = widest > phi.dims[l] ? widest : phi.dims[l];
     *bytes = sizeof(float) * 2 * kTile * (size_t)(widest + 1);
     const void* fn = paged ? reinterpret_cast<const void*>(&encode_bulk_kernel<true>)
                            : reinterpret_cast<const void*>(&encode_bulk_kernel<false>);

@@ -101,7 +101,8 @@ def test_topk_wide_long_context_units_of_512_and_1024():
     topk_wide_case(2, 40000, 1000, batch=64, Hq=2, Hkv=1)                           # many lanes: units of 1024
 
 
-@pytest.mark.parametrize("bits,dims", [(64, (128, 128, 64)), (128, (128, 128)), (256, (128, 64, 128, 256))])
+@pytest.mark.parametrize("bits,dims", [(64, (128, 128, 64)), (128, (128, 128)), (256, (128, 64, 128, 256)),
+                                       (512, (128, 128, 512)), (512, (128, 512))])
 def test_wide_mapping_and_whole_step(bits, dims):
     """encode_keys (bulk and append), encode_query, SCORE + TOPK, GATHER-ATT with b-bit signatures."""
     import paper_2412_14468_amd as ha
@@ -180,13 +181,17 @@ def test_wide_mapping_and_whole_step(bits, dims):
     gu.assert_out_close(out, res["out"], f"gather_attend, {bits}-bit signatures")
 
 
-def test_512_bit_mapping_is_refused_and_bad_width_rejected():
+def test_bad_widths_rejected():
     import paper_2412_14468_amd as ha
     with pytest.raises(ha.HashAttnError, match="bits"):
         ha.Context(4, 1, 1, 1024, 16, bits=96)
     ctx = ha.Context(4, 1, 1, 1024, 16, bits=512)
-    w = [torch.zeros((4, 128, 512), dtype=torch.float32, device=DEV)]
     q = torch.zeros((1, 4, 128), dtype=torch.bfloat16, device=DEV)
     qc = torch.zeros((1, 4, 16), dtype=torch.int32, device=DEV)
-    with pytest.raises(ha.HashAttnError, match="at most 256 bits"):
+    w = [torch.zeros((4, 128, 256), dtype=torch.float32, device=DEV)]              # 256 outputs in a 512-bit context
+    with pytest.raises(ha.HashAttnError, match="512 outputs"):
+        ctx.hashattn_encode_query(ha.Mlp(w), q, 1, qc)
+    w = [torch.zeros((4, 128, 512), dtype=torch.float32, device=DEV),             # hidden layers stop at 256
+         torch.zeros((4, 512, 512), dtype=torch.float32, device=DEV)]
+    with pytest.raises(ha.HashAttnError, match="hidden width"):
         ctx.hashattn_encode_query(ha.Mlp(w), q, 1, qc)
