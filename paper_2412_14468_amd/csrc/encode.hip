@@ -69,12 +69,12 @@ __device__ int mlp_gemv(const MlpView& phi, int head, float (*act)[kVecPerBlock]
 // MODE 0: queries.  x = q [B][H][128]; codes -> q_codes [B][H]; vector index = b.
 // MODE 1: appended keys.  x = k_new [B][H][n_new][128]; vector index = b * n_new + j; the K and V rows
 //         are copied to cache position seq_lens[b] + j and the code stored there.
-template <int MODE, int WD>
+template <int MODE, int WD, int VB>
 __device__ __forceinline__ void load_vectors(float (*act0)[WD], int n_heads, int head, int v0,
                                              const uint16_t* __restrict__ x, int n_vec, int n_new)
 {
     const int tid = threadIdx.x;
-    for (int o = tid; o < kVecPerBlock * kHeadDim; o += 256) {
+    for (int o = tid; o < VB * kHeadDim; o += 256) {
         const int v = o / kHeadDim, i = o - v * kHeadDim, vec = v0 + v;
         float val = 0.f;
         if (vec < n_vec) {
@@ -87,8 +87,8 @@ __device__ __forceinline__ void load_vectors(float (*act0)[WD], int n_heads, int
     }
 }
 
-// a: [kVecPerBlock][WD] pre-sign activations of the last layer
-template <int MODE, bool PAGED, int WD>
+// a: [VB][WD] pre-sign activations of the last layer of the block's VB vectors
+template <int MODE, bool PAGED, int WD, int VB>
 __device__ __forceinline__ void store_codes(const float (*a)[WD], int n_heads, int head, int v0,
                                             const uint16_t* __restrict__ x, const uint16_t* __restrict__ v_new,
                                             int n_vec, int n_new, uint32_t* __restrict__ q_codes,
@@ -97,8 +97,8 @@ __device__ __forceinline__ void store_codes(const float (*a)[WD], int n_heads, i
     // thread (v = tid / 32, j = tid % 32) owns bit j of every code word of vector v (unit 32 w + j of
     // word w); a wave ballot packs one word of two vectors
     const int tid = threadIdx.x;
-    const int v = tid >> 5, j = tid & 31, vec = v0 + v;
-    const bool live = vec < n_vec;
+    const int slot = tid >> 5, j = tid & 31, v = min(slot, VB - 1), vec = v0 + v;
+    const bool live = slot < VB && vec < n_vec;
     const int b = MODE == 0 ? vec : vec / n_new, jn = MODE == 0 ? 0 : vec - b * n_new;
     int64_t row = 0;
     if constexpr (MODE == 1) {
@@ -154,10 +154,10 @@ __global__ __launch_bounds__(256) void encode_vec_kernel(MlpView phi, int n_head
     __shared__ float act[2][kVecPerBlock][kMaxWidth];
     __shared__ float red[kVecPerBlock * 256];
     const int head = blockIdx.x, v0 = blockIdx.y * kVecPerBlock;
-    load_vectors<MODE, kMaxWidth>(act[0], n_heads, head, v0, x, n_vec, n_new);
+    load_vectors<MODE, kMaxWidth, kVecPerBlock>(act[0], n_heads, head, v0, x, n_vec, n_new);
     __syncthreads();
     const int cur = mlp_gemv(phi, head, act, red);
-    store_codes<MODE, PAGED, kMaxWidth>(act[cur], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap,
+    store_codes<MODE, PAGED, kMaxWidth, kVecPerBlock>(act[cur], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap,
                              phi.dims[phi.n_layers] / kBits);
     if constexpr (MODE == 1) finish_append(done, c.seq_lens, n_vec / n_new, n_new);
 }
@@ -174,7 +174,7 @@ __device__ __forceinline__ void fetch_weights(const float* __restrict__ W, float
     for (int i = 0; i < SPAN; ++i) w[i] = W[(int64_t)(p * SPAN + i) * DOUT + j];
 }
 
-// VT: vectors of the block that are worked on (slots VT.. of `in` and `out` are left alone)
+// VT: vectors per block
 template <int DI, int DOUT, int VT>
 __device__ __forceinline__ void gemv_layer(const float (&w)[DI * DOUT / 256], const float* __restrict__ bias,
                                            const float (*in)[kFixedWidth], float (*out)[kFixedWidth], float* red,
@@ -190,13 +190,13 @@ __device__ __forceinline__ void gemv_layer(const float (&w)[DI * DOUT / 256], co
 #pragma unroll
         for (int v = 0; v < VT; ++v) acc[v] = fmaf(in[v][p * SPAN + i], w[i], acc[v]);
 #pragma unroll
-    for (int v = 0; v < VT; ++v) red[(p * kVecPerBlock + v) * DOUT + j] = acc[v];
+    for (int v = 0; v < VT; ++v) red[(p * VT + v) * DOUT + j] = acc[v];
     __syncthreads();
     for (int o = tid; o < VT * DOUT; o += 256) {
         const int v = o / DOUT, jj = o - v * DOUT;
         float z = 0.f;
 #pragma unroll
-        for (int pp = 0; pp < PARTS; ++pp) z += red[(pp * kVecPerBlock + v) * DOUT + jj];
+        for (int pp = 0; pp < PARTS; ++pp) z += red[(pp * VT + v) * DOUT + jj];
         if (bias) z += bias[jj];
         out[v][jj] = last ? z : silu(z);
     }
@@ -204,8 +204,9 @@ __device__ __forceinline__ void gemv_layer(const float (&w)[DI * DOUT / 256], co
 }
 
 // NL layers: 128 -> D1 -> D2 -> 32 (NL = 3), 128 -> D1 -> 32 (NL = 2), 128 -> 32 (NL = 1).
-// VT = 1 when the block has a single vector (one query per head at batch 1): the other seven slots
-// would cost seven times the LDS reads and multiplies for nothing.
+// VT vectors per block: every vector costs a block its LDS reads and multiplies one after the other, so
+// a launch with few vectors spreads them over more blocks (the weights are then read VT times less often
+// than once per vector, from L2 after the first block of a head).
 template <int MODE, bool PAGED, int NL, int D1, int D2, int VT>
 __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int n_heads,
                                                                const uint16_t* __restrict__ x,
@@ -213,9 +214,9 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
                                                                int n_new, uint32_t* __restrict__ q_codes,
                                                                KvView c, int n_cap, int32_t* __restrict__ done)
 {
-    __shared__ float act[2][kVecPerBlock][kFixedWidth];
-    __shared__ float red[kVecPerBlock * 256];
-    const int head = blockIdx.x, v0 = blockIdx.y * kVecPerBlock;
+    __shared__ float act[2][VT][kFixedWidth];
+    __shared__ float red[VT * 256];
+    const int head = blockIdx.x, v0 = blockIdx.y * VT;
     constexpr int O0 = NL == 1 ? kBits : D1;            // outputs of layer 0
     constexpr int I1 = D1, O1 = NL == 2 ? kBits : D2;   // layer 1 (NL >= 2)
     constexpr int I2 = D2;                              // layer 2 (NL == 3), 32 outputs
@@ -225,39 +226,51 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
     fetch_weights<kHeadDim, O0>(phi.W[0] + (int64_t)head * kHeadDim * O0, w0);
     if constexpr (NL >= 2) fetch_weights<I1, O1>(phi.W[1] + (int64_t)head * I1 * O1, w1);
     if constexpr (NL == 3) fetch_weights<I2, kBits>(phi.W[2] + (int64_t)head * I2 * kBits, w2);
-    load_vectors<MODE, kFixedWidth>(act[0], n_heads, head, v0, x, n_vec, n_new);
+    load_vectors<MODE, kFixedWidth, VT>(act[0], n_heads, head, v0, x, n_vec, n_new);
     __syncthreads();
     gemv_layer<kHeadDim, O0, VT>(w0, phi.bias[0] ? phi.bias[0] + (int64_t)head * O0 : nullptr, act[0], act[1], red, NL == 1);
     if constexpr (NL >= 2)
         gemv_layer<I1, O1, VT>(w1, phi.bias[1] ? phi.bias[1] + (int64_t)head * O1 : nullptr, act[1], act[0], red, NL == 2);
     if constexpr (NL == 3)
         gemv_layer<I2, kBits, VT>(w2, phi.bias[2] ? phi.bias[2] + (int64_t)head * kBits : nullptr, act[0], act[1], red, true);
-    store_codes<MODE, PAGED, kFixedWidth>(act[NL & 1], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap);
+    store_codes<MODE, PAGED, kFixedWidth, VT>(act[NL & 1], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap);
     if constexpr (MODE == 1) finish_append(done, c.seq_lens, n_vec / n_new, n_new);
 }
 
+template <int MODE, bool PAGED, int NL, int D1, int D2>
+void launch_fixed(int vt, const MlpView& phi, int n_heads, const uint16_t* x, const uint16_t* v_new, int n_vec,
+                  int n_new, uint32_t* q_codes, const KvView& c, int n_cap, int32_t* done, hipStream_t stream)
+{
+    const dim3 grid(n_heads, (n_vec + vt - 1) / vt);
+    switch (vt) {
+    case 1: encode_vec_fixed_kernel<MODE, PAGED, NL, D1, D2, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done); break;
+    case 2: encode_vec_fixed_kernel<MODE, PAGED, NL, D1, D2, 2><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done); break;
+    case 4: encode_vec_fixed_kernel<MODE, PAGED, NL, D1, D2, 4><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done); break;
+    default: encode_vec_fixed_kernel<MODE, PAGED, NL, D1, D2, 8><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done); break;
+    }
+}
+
 template <int MODE, bool PAGED>
-void launch_encode_vec(const MlpView& phi, dim3 grid, int n_heads, const uint16_t* x, const uint16_t* v_new,
+void launch_encode_vec(const MlpView& phi, int n_heads, const uint16_t* x, const uint16_t* v_new,
                        int n_vec, int n_new, uint32_t* q_codes, const KvView& c, int n_cap, int32_t* done,
                        hipStream_t stream)
 {
     const int nl = phi.n_layers, d1 = phi.dims[1], d2 = phi.dims[2];
-    if (phi.dims[nl] != kBits)           // wider signatures: the general kernel
+    // vectors per block: the fewest (of 2, 4, 8; 1 for a single vector) that keep the launch within 512
+    // blocks (measured at 16 and 64 vectors for 32 heads and at 16 for 8)
+    int vt = n_vec == 1 ? 1 : 2;
+    while (vt < kVecPerBlock && (int64_t)n_heads * ((n_vec + vt - 1) / vt) > 512) vt *= 2;
+    const bool narrow = phi.dims[nl] == kBits;          // wider signatures take the general kernel
+    if (narrow && nl == 1)
+        launch_fixed<MODE, PAGED, 1, 32, 32>(vt, phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done, stream);
+    else if (narrow && nl == 2 && d1 == 128)
+        launch_fixed<MODE, PAGED, 2, 128, 32>(vt, phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done, stream);
+    else if (narrow && nl == 3 && d1 == 128 && d2 == 128)
+        launch_fixed<MODE, PAGED, 3, 128, 128>(vt, phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done, stream);
+    else {
+        const dim3 grid(n_heads, (n_vec + kVecPerBlock - 1) / kVecPerBlock);
         encode_vec_kernel<MODE, PAGED><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
-    else if (nl == 1 && n_vec == 1)
-        encode_vec_fixed_kernel<MODE, PAGED, 1, 32, 32, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
-    else if (nl == 1)
-        encode_vec_fixed_kernel<MODE, PAGED, 1, 32, 32, kVecPerBlock><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
-    else if (nl == 2 && d1 == 128 && n_vec == 1)
-        encode_vec_fixed_kernel<MODE, PAGED, 2, 128, 32, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
-    else if (nl == 2 && d1 == 128)
-        encode_vec_fixed_kernel<MODE, PAGED, 2, 128, 32, kVecPerBlock><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
-    else if (nl == 3 && d1 == 128 && d2 == 128 && n_vec == 1)
-        encode_vec_fixed_kernel<MODE, PAGED, 3, 128, 128, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
-    else if (nl == 3 && d1 == 128 && d2 == 128)
-        encode_vec_fixed_kernel<MODE, PAGED, 3, 128, 128, kVecPerBlock><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
-    else
-        encode_vec_kernel<MODE, PAGED><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
+    }
 }
 
 __global__ void bump_seq_lens_kernel(int32_t* seq_lens, int batch, int n_new)
@@ -408,9 +421,8 @@ hipError_t bulk_lds_setup(const MlpView& phi, bool paged, size_t* bytes)
 hipError_t launch_encode_query(const MlpView& phi, const uint16_t* q, int batch, int n_heads,
                                uint32_t* q_codes, hipStream_t stream)
 {
-    const dim3 grid(n_heads, (batch + kVecPerBlock - 1) / kVecPerBlock);
     KvView none{};
-    launch_encode_vec<0, false>(phi, grid, n_heads, q, nullptr, batch, 1, q_codes, none, 0, nullptr, stream);
+    launch_encode_vec<0, false>(phi, n_heads, q, nullptr, batch, 1, q_codes, none, 0, nullptr, stream);
     return hipGetLastError();
 }
 
@@ -426,11 +438,10 @@ hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
         if (n_new * batch <= 4 * kVecPerBlock) {
             // decode-time append: one GEMV-shaped launch writes rows and codes and moves the lengths
             const int n_vec = (int)(batch * n_new);
-            const dim3 grid(H, (n_vec + kVecPerBlock - 1) / kVecPerBlock);
             if (paged)
-                launch_encode_vec<1, true>(phi, grid, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len, sc->append_done, stream);
+                launch_encode_vec<1, true>(phi, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len, sc->append_done, stream);
             else
-                launch_encode_vec<1, false>(phi, grid, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len, sc->append_done, stream);
+                launch_encode_vec<1, false>(phi, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len, sc->append_done, stream);
         } else {
             const dim3 cgrid((unsigned)((n_new * 16 + 255) / 256), H, batch);
             const dim3 egrid((unsigned)((n_new + kTile - 1) / kTile), H, batch);
