@@ -54,10 +54,12 @@ __device__ __forceinline__ void load_chunk(const KvView& c, int b, int kvh, int 
     }
 }
 
-// CHECKED: only tokens t with lo <= t < hi are counted.
+// CHECKED: only tokens t with lo <= t < hi are counted.  nqc: the complemented query codes, so that the
+// bit count of the xor is the score itself (three instructions and one LDS add per token and head:
+// xor, count, shift-or into the address).
 template <int G, bool CHECKED>
 __device__ __forceinline__ void count_chunk(const uint4 (&cw)[4], int base, int lo, int hi, int lane,
-                                            const uint32_t (&qc)[G], unsigned* mine)
+                                            const uint32_t (&nqc)[G], unsigned* mine)
 {
 #pragma unroll
     for (int it = 0; it < 4; ++it) {
@@ -68,7 +70,7 @@ __device__ __forceinline__ void count_chunk(const uint4 (&cw)[4], int base, int 
             if (!CHECKED || (t0 + e >= lo && t0 + e < hi)) {
 #pragma unroll
                 for (int j = 0; j < G; ++j)       // score = popcount of the agreeing bits
-                    atomicAdd(&mine[(j * kBins + __popc(~(w[e] ^ qc[j]))) * kBinCopies], 1u);
+                    atomicAdd(&mine[(j * kBins + __popc(w[e] ^ nqc[j])) * kBinCopies], 1u);
             }
         }
     }
@@ -113,9 +115,9 @@ __global__ __launch_bounds__(WPB * kWave) void score_hist_kernel(KvView c, const
     if constexpr (PAGED) {
         if (active) load_chunk<PAGED, 4>(c, b, kvh, (int)t_begin, t_end, lane, cw);
     }
-    uint32_t qc[G];
-#pragma unroll
-    for (int j = 0; j < G; ++j) qc[j] = (uint32_t)uniform(qraw[j]);
+    uint32_t qc[G];                                        // complemented (see count_chunk); made uniform after the
+#pragma unroll                                             // complement so that it stays one
+    for (int j = 0; j < G; ++j) qc[j] = (uint32_t)uniform(~qraw[j]);
     for (int i = tid; i < G * kBins * kBinCopies; i += (WPB * kWave)) hist[i] = 0u;
     __syncthreads();
 
