@@ -130,6 +130,34 @@ __device__ __forceinline__ int lanes_below(uint64_t mask)
 
 __device__ __forceinline__ int uniform(int x) { return __builtin_amdgcn_readfirstlane(x); }
 
+// The lowest `take` set bits of x.
+__device__ __forceinline__ unsigned lowest_bits(unsigned x, int take)
+{
+    unsigned r = 0;
+    for (int i = 0; i < take && x; ++i) {
+        const unsigned low = x & (0u - x);
+        r |= low;
+        x ^= low;
+    }
+    return r;
+}
+
+// Token ids of the set bits of m (bit p = token t0 + p), written to out[rank], out[rank + 1], ...
+// At 1/32 density a lane rarely holds more than three of its sixteen tokens: three rounds without a
+// branch (a lane with nothing left just does not store), then a loop for the rest.
+__device__ __forceinline__ void emit_ids(unsigned m, int rank, int t0, int pitch, int32_t* __restrict__ out)
+{
+    auto round = [&]() {
+        if (m != 0u && rank < pitch) out[rank] = t0 + (__ffs((int)m) - 1);
+        rank += m != 0u ? 1 : 0;
+        m &= m - 1u;                                   // clears the lowest set bit; 0 stays 0
+    };
+    round();
+    round();
+    round();
+    while (__builtin_amdgcn_ballot_w64(m != 0u) != 0ull) round();
+}
+
 // Workgroups go to the eight XCDs round-robin in launch order, x fastest.  With the piece index
 // of a (sequence, head) in blockIdx.x and a piece count that divides (or is divided by) eight,
 // piece p of every list would land on the same XCD, and in a batch of mixed lengths the high

@@ -216,34 +216,6 @@ __device__ __forceinline__ void to_lane_runs(const uint4 (&cw)[NIT], uint4* stag
     }
 }
 
-// The lowest `take` set bits of x.
-__device__ __forceinline__ unsigned lowest_bits(unsigned x, int take)
-{
-    unsigned r = 0;
-    for (int i = 0; i < take && x; ++i) {
-        const unsigned low = x & (0u - x);
-        r |= low;
-        x ^= low;
-    }
-    return r;
-}
-
-// Token ids of the set bits of m (bit p = token t0 + p), written to out[rank], out[rank + 1], ...
-// At 1/32 density a lane rarely holds more than three of its sixteen tokens: three rounds without a
-// branch (a lane with nothing left just does not store), then a loop for the rest.
-__device__ __forceinline__ void emit_ids(unsigned m, int rank, int t0, int pitch, int32_t* __restrict__ out)
-{
-    auto round = [&]() {
-        if (m != 0u && rank < pitch) out[rank] = t0 + (__ffs((int)m) - 1);
-        rank += m != 0u ? 1 : 0;
-        m &= m - 1u;                                   // clears the lowest set bit; 0 stays 0
-    };
-    round();
-    round();
-    round();
-    while (__builtin_amdgcn_ballot_w64(m != 0u) != 0ull) round();
-}
-
 // NIT: 16-byte loads per lane and chunk (unit_tokens = 256 NIT for NIT < 4); NCH: chunks of 1024
 // tokens per unit (unit_tokens = 1024 NCH, NIT = 4).
 template <int G, bool PAGED, int NIT, int NCH, int WPB>

@@ -13,8 +13,9 @@
 //   - the select makes two passes over per-step ballot masks instead of two passes over the codes:
 //     the first pass scores the unit once, keeps for every 64-token step and head the masks
 //     "score > T" and "score == T" in LDS and counts them; after the waves of the block have
-//     exchanged their counts, the second pass turns masks into ranks (ties in token order against
-//     the wave's share of the quota) and stores the ids.
+//     exchanged their counts, the second pass gives every lane a run of consecutive tokens, cut out
+//     of those masks, and ranks and stores the ids as the 32-bit select does (ties in token order
+//     against the wave's share of the quota).
 // Units are 256, 512 or 1024 tokens (16 steps of masks per wave at most).
 #include "kernels.hpp"
 
@@ -284,26 +285,33 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
     __syncthreads();
     if (!active) return;
 
-    // ---- pass 2: ranks from the masks; a tie is taken while the wave's share of the quota lasts
+    // ---- pass 2: every lane takes a run of unit_tokens / 64 consecutive tokens (4, 8 or 16), cuts its
+    // bits out of the step masks and proceeds as the 32-bit select does: ties are taken in token order
+    // while the wave's share of the quota lasts, a wave scan gives the lane's first slot, and the ids
+    // go out a few rounds at a time
+    const int tpl = unit_tokens >> 6;
+    const int run0 = lane * tpl;                                     // first token of the run inside the unit
+    const int rs = run0 >> 6, roff = run0 & 63;                      // its step and first bit there
+    const unsigned run_bits = rs < n_steps ? (1u << tpl) - 1u : 0u;  // steps past the unit's end hold stale masks
 #pragma unroll
     for (int j = 0; j < G; ++j) {
         const int gt_before = wave_sum_i32(lane < wave ? wgt[lane][j] : 0);
         const int eq_before = wave_sum_i32(lane < wave ? weq[lane][j] : 0);
         const int quota_b = uniform(quotab[j]);
         const int quota_w = quota_b == kAllTies ? kAllTies : max(0, quota_b - eq_before);
-        int start = uniform(posb[j]) + gt_before + min(eq_before, quota_b);
-        int seen = 0;
-        int32_t* out = idx + (bh0 + j) * pitch;
-        for (int s = 0; s < n_steps; ++s) {
-            const uint64_t g_mask = m_gt[wave][s][j], e_mask = m_eq[wave][s][j];
-            const bool tie = (e_mask >> lane) & 1ull;
-            const bool take = ((g_mask >> lane) & 1ull) || (tie && seen + lanes_below(e_mask) < quota_w);
-            const uint64_t t_mask = __ballot(take);
-            const int rank = start + lanes_below(t_mask);
-            if (take && rank < pitch) out[rank] = (int)t_begin + s * kWave + lane;
-            start += __popcll(t_mask);
-            seen += __popcll(e_mask);
+        const int start = uniform(posb[j]) + gt_before + min(eq_before, quota_b);
+        unsigned sel = (unsigned)(m_gt[wave][rs][j] >> roff) & run_bits;
+        const unsigned tie = (unsigned)(m_eq[wave][rs][j] >> roff) & run_bits;
+        if (quota_w == kAllTies) {
+            sel |= tie;
+        } else if (quota_w > 0) {
+            const int mine = __popc(tie);
+            const int incl = wave_incl_scan_i32(mine);
+            sel |= lowest_bits(tie, max(0, min(mine, quota_w - (incl - mine))));
         }
+        const int cnt = __popc(sel);
+        const int incl = wave_incl_scan_i32(cnt);
+        emit_ids(sel, start + incl - cnt, (int)t_begin + run0, pitch, idx + (bh0 + j) * pitch);
     }
 }
 
