@@ -186,6 +186,21 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
     const bool active = t_begin < n && !nothing;
     const int t_end = (int)min((int64_t)n, t_begin + unit_tokens);
 
+    // the first codes are requested before the tables are summed: they are not needed until the
+    // threshold is known, and by then they have arrived
+    const int n_steps = active ? (t_end - (int)t_begin + kWave - 1) / kWave : 0;
+    auto fetch = [&](int t) {                                        // the code of token t, zeros if it is not scored
+        CodeWords<W> r;
+#pragma unroll
+        for (int i = 0; i < W; ++i) r.w[i] = 0u;
+        if (active && t < t_end && t >= lo && t < hi) r = load_code<PAGED, W>(c, b, kvh, t);
+        return r;
+    };
+    constexpr int kDepth = depth_of(W);
+    CodeWords<W> ring[kDepth];
+#pragma unroll
+    for (int d = 0; d < kDepth; ++d) ring[d] = fetch((int)t_begin + d * kWave + lane);
+
     if (tid < G) thr[tid] = -1;
     if (tid < G * W) qs[tid] = q_codes[bh0 * W + tid];
     // whole-sequence cumulative counts: one thread per (head, score), blocks summed in a loop
@@ -245,18 +260,6 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
     int T[G], cgt[G], ceq[G];
 #pragma unroll
     for (int j = 0; j < G; ++j) { T[j] = uniform(thr[j]); cgt[j] = ceq[j] = 0; }
-    const int n_steps = active ? (t_end - (int)t_begin + kWave - 1) / kWave : 0;
-    auto fetch = [&](int t) {                                        // the code of token t, zeros if it is not scored
-        CodeWords<W> r;
-#pragma unroll
-        for (int i = 0; i < W; ++i) r.w[i] = 0u;
-        if (t < t_end && t >= lo && t < hi) r = load_code<PAGED, W>(c, b, kvh, t);
-        return r;
-    };
-    constexpr int kDepth = depth_of(W);
-    CodeWords<W> ring[kDepth];
-#pragma unroll
-    for (int d = 0; d < kDepth; ++d) ring[d] = fetch((int)t_begin + d * kWave + lane);
     for (int s0 = 0; s0 < n_steps; s0 += kDepth) {
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) {
