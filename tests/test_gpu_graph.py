@@ -59,3 +59,34 @@ def test_graph_replays_equal_eager(append):
         float(scratch.sum())                                 # a library reduction and a host sync in between
     if append:
         assert s.seq_lens.cpu().tolist() == (lens0 + 1).cpu().tolist()
+
+
+def test_two_contexts_on_two_streams():
+    """Each context owns its scratch: steps of two contexts issued on two streams at the same time give
+    what each gives alone."""
+    import paper_2412_14468_amd as ha
+    from paper_2412_14468_amd import runner
+    states, ctxs, refs = [], [], []
+    for i, (n, k, batch) in enumerate(((30000, 900, 2), (9000, 300, 5))):
+        cfg = W.scaled(W.c1(context=n, k=k, batch=batch), name=f"pair{i}")
+        t = W.device_tensors(cfg, W.BASE_SEED + 200 + i)
+        s = runner.layer_from_tensors(t)
+        ctx = ha.Context(cfg.n_q_heads, cfg.n_kv_heads, cfg.batch, t["n_max"], s.k_max)
+        runner.build_key_codes(ctx, s)
+        runner.decode_step(ctx, s)
+        torch.cuda.synchronize()
+        refs.append((s.idx.clone(), s.count.clone(), s.out.clone()))
+        states.append(s)
+        ctxs.append(ctx)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    for s in states:
+        s.idx.fill_(-1); s.count.fill_(-1); s.out.zero_()
+    torch.cuda.synchronize()
+    for _ in range(3):                                        # interleaved submissions, no waits in between
+        for ctx, s, st in zip(ctxs, states, streams):
+            with torch.cuda.stream(st):
+                runner.decode_step(ctx, s)
+    torch.cuda.synchronize()
+    for s, (idx, count, out) in zip(states, refs):
+        assert torch.equal(s.count, count) and torch.equal(s.idx, idx)
+        assert torch.equal(s.out.view(torch.int16), out.view(torch.int16))
