@@ -185,7 +185,7 @@ def main():
         del src
 
     def one_step(s):
-        if cfg.append:                       # every step appends to a cache that holds N - 1 tokens
+        if cfg.append:                       # every step appends to a cache that holds N - 1 tokens (the copy is timed too)
             s.seq_lens.copy_(s.lens0_dev)
             s.cache.max_seq_len = s.max_len0
         runner.decode_step(ctx, s, append=cfg.append)
