@@ -234,7 +234,7 @@ __global__ __launch_bounds__(WPB * kWave) void topk_select_kernel(KvView c, cons
     constexpr int kRowsPerPass = (WPB * kWave) / kCumRow;           // 30 table rows are read side by side
     constexpr int kPairs = (G + 1) / 2;                        // two heads share a packed wave sum / scan
     extern __shared__ uint4 stage_all[];                       // NIT > 1: 64 * NIT slots per wave
-    __shared__ int tot[G * kCumRow];
+    __shared__ int tot[G * kCumRow], bef[G * kCumRow], own[G * kCumRow];   // cumulative counts: sequence, blocks before this one, this block
     __shared__ int thr[G], posb[G], quotab[G];                 // per head: T, first output slot and tie quota of the block
     __shared__ int wcnt[WPB][kPairs], weq[WPB][kPairs];      // per wave: selected / tied tokens, two heads per int
     const int tid = threadIdx.x, wave = uniform(tid >> 6), lane = tid & 63;    // wave: scalar, so are the token ranges
@@ -272,7 +272,7 @@ __global__ __launch_bounds__(WPB * kWave) void topk_select_kernel(KvView c, cons
     uint32_t qc[G];
 #pragma unroll
     for (int j = 0; j < G; ++j) qc[j] = (uint32_t)uniform(qraw[j]);
-    for (int i = tid; i < G * kCumRow; i += (WPB * kWave)) tot[i] = 0;
+    for (int i = tid; i < G * kCumRow; i += (WPB * kWave)) tot[i] = bef[i] = own[i] = 0;
 
     const int n = min(n_raw, n_cap);
     // the first `lo` and the tokens from `hi` on are always taken; k counts the tokens retrieved in between
@@ -288,18 +288,25 @@ __global__ __launch_bounds__(WPB * kWave) void topk_select_kernel(KvView c, cons
     }
     __syncthreads();
 
-    // ---- whole-sequence cumulative counts per head: sum of the per-block rows (stale rows of blocks
-    // beyond the sequence are dropped here)
+    // ---- cumulative counts per head from the per-block rows, in one trip to memory: over the whole
+    // sequence, over the blocks before this one, and this block's own row (stale rows of blocks beyond
+    // the sequence are dropped here)
     if (srow < kRowsPerPass) {
 #pragma unroll
         for (int j = 0; j < G; ++j) {
-            int v = 0;
+            int v = 0, vb = 0;
+            auto take = [&](int blk, int x) {
+                v += x;
+                if (blk < bx) vb += x;
+                if (blk == bx) own[j * kCumRow + scol] = x;
+            };
 #pragma unroll
             for (int u = 0; u < kPrefetch; ++u)
-                if (srow + u * kRowsPerPass < n_blocks) v += tv[j][u];
+                if (srow + u * kRowsPerPass < n_blocks) take(srow + u * kRowsPerPass, tv[j][u]);
             for (int blk = srow + kPrefetch * kRowsPerPass; blk < n_blocks; blk += kRowsPerPass)   // very long contexts
-                v += blk_cum[((bh0 + j) * blocks_pitch + blk) * kCumRow + scol];
+                take(blk, blk_cum[((bh0 + j) * blocks_pitch + blk) * kCumRow + scol]);
             if (v) atomicAdd(&tot[j * kCumRow + scol], v);
+            if (vb) atomicAdd(&bef[j * kCumRow + scol], vb);
         }
     }
     __syncthreads();
@@ -307,22 +314,17 @@ __global__ __launch_bounds__(WPB * kWave) void topk_select_kernel(KvView c, cons
     // ---- selection parameters: wave j works them out for head j
     for (int j = wave; j < G; j += WPB) {
         const int64_t bh = bh0 + j;
-        const int32_t* tab = blk_cum + bh * blocks_pitch * kCumRow;
         const int cum = lane < kCumRow ? tot[j * kCumRow + lane] : 0;   // #{score >= lane} over the sequence
         int T = kBins, r = 0, gt = 0, ge = 0, own_gt = 0, own_ge = 0;
         if (k > 0) {
             const uint64_t ge_k = __ballot(lane < kBins && cum >= k);   // lane 0 is set: cum(0) = n >= k
             T = 63 - __clzll((long long)(ge_k | 1ull));
             r = k - __shfl(cum, T + 1, kWave);                          // slot 33 holds 0
-            for (int blk = lane; blk < bx; blk += kWave) {
-                ge += tab[blk * kCumRow + T];
-                gt += tab[blk * kCumRow + T + 1];
-            }
-            own_ge = tab[bx * kCumRow + T];
-            own_gt = tab[bx * kCumRow + T + 1];
+            ge = bef[j * kCumRow + T];                                  // #{score >= T} before this block
+            gt = bef[j * kCumRow + T + 1];
+            own_ge = own[j * kCumRow + T];
+            own_gt = own[j * kCumRow + T + 1];
         }
-        gt = wave_sum_i32(gt);                                          // #{score > T} before this block
-        ge = wave_sum_i32(ge);
         if (lane == 0) {
             const int eq_before = ge - gt, own_eq = own_ge - own_gt;    // #{score == T} before / inside this block
             const int left = r - eq_before;                             // tie quota still open at this block

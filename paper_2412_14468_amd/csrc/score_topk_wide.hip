@@ -165,8 +165,8 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
                                                                     uint8_t* __restrict__ threshold)
 {
     constexpr int kBinsW = bins_of(W), kRow = kBinsW + 1;
-    __shared__ int tot[G * kRow];
-    __shared__ int thr[G], posb[G], quotab[G];
+    __shared__ int tot[G * kRow], bef[G * kRow];
+    __shared__ int thr[G], posb[G], quotab[G], own_ge_s[G], own_gt_s[G];
     __shared__ int wgt[kWpb][G], weq[kWpb][G];                     // per wave: tokens taken for sure / tied
     __shared__ uint64_t m_gt[kWpb][kMaxSteps][G], m_eq[kWpb][kMaxSteps][G];
     __shared__ uint32_t qs[G * W];
@@ -201,21 +201,35 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) ring[d] = fetch((int)t_begin + d * kWave + lane);
 
-    if (tid < G) thr[tid] = -1;
+    if (tid < G) { thr[tid] = -1; own_ge_s[tid] = own_gt_s[tid] = 0; }
     if (tid < G * W) qs[tid] = q_codes[bh0 * W + tid];
-    // whole-sequence cumulative counts: one thread per (head, score), blocks summed in a loop
-    for (int i = tid; i < G * kRow; i += kThreads) {
-        const int j = i / kRow, col = i - j * kRow;
-        const int32_t* p = blk_cum + (bh0 + j) * blocks_pitch * kRow + col;
-        int v = 0;
-        for (int blk0 = 0; blk0 < n_blocks; blk0 += 16) {           // sixteen independent loads per trip to memory
-            int part[16];
+    // Cumulative counts from the per-block rows in one trip to memory, one thread per (head, score):
+    // over the whole sequence (tot), over the blocks before this one (bef), and this block's own row
+    // (kept in registers until the threshold says which two of its entries matter).
+    constexpr int kIter = (G * kRow + kThreads - 1) / kThreads;
+    int own_r[kIter];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) part[u] = blk0 + u < n_blocks ? p[(int64_t)(blk0 + u) * kRow] : 0;
+    for (int it = 0; it < kIter; ++it) {
+        const int i = tid + it * kThreads;
+        own_r[it] = 0;
+        if (i < G * kRow) {
+            const int j = i / kRow, col = i - j * kRow;
+            const int32_t* p = blk_cum + (bh0 + j) * blocks_pitch * kRow + col;
+            int v = 0, vb = 0;
+            for (int blk0 = 0; blk0 < n_blocks; blk0 += 16) {           // sixteen independent loads per trip to memory
+                int part[16];
 #pragma unroll
-            for (int u = 0; u < 16; ++u) v += part[u];
+                for (int u = 0; u < 16; ++u) part[u] = blk0 + u < n_blocks ? p[(int64_t)(blk0 + u) * kRow] : 0;
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    v += part[u];
+                    if (blk0 + u < bx) vb += part[u];
+                    if (blk0 + u == bx) own_r[it] = part[u];
+                }
+            }
+            tot[i] = v;
+            bef[i] = vb;
         }
-        tot[i] = v;
     }
     __syncthreads();
     // threshold: the largest score s with C(s) >= k (C(0) = number of scored tokens >= k)
@@ -226,40 +240,54 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
         }
     }
     __syncthreads();
-    for (int j = wave; j < G; j += kWpb) {
-        const int64_t bh = bh0 + j;
-        const int32_t* tab = blk_cum + bh * blocks_pitch * kRow;
-        const int T = k > 0 ? thr[j] : kBinsW;                           // k = 0: nothing reaches the threshold
-        int r = 0, gt = 0, ge = 0, own_gt = 0, own_ge = 0;
-        if (k > 0) {
-            r = k - tot[j * kRow + T + 1];
-            for (int blk = lane; blk < bx; blk += kWave) {
-                ge += tab[(int64_t)blk * kRow + T];
-                gt += tab[(int64_t)blk * kRow + T + 1];
+    if (k > 0) {
+#pragma unroll
+        for (int it = 0; it < kIter; ++it) {
+            const int i = tid + it * kThreads;
+            if (i < G * kRow) {
+                const int j = i / kRow, col = i - j * kRow;
+                if (col == thr[j]) own_ge_s[j] = own_r[it];
+                if (col == thr[j] + 1) own_gt_s[j] = own_r[it];
             }
-            own_ge = tab[(int64_t)bx * kRow + T];
-            own_gt = tab[(int64_t)bx * kRow + T + 1];
         }
-        gt = wave_sum_i32(gt);
-        ge = wave_sum_i32(ge);
-        if (lane == 0) {
-            const int eq_before = ge - gt, own_eq = own_ge - own_gt, left = r - eq_before;
-            const int bs = (int)min((int64_t)n, (int64_t)bx * block_tokens);   // always-kept tokens before this block
-            thr[j] = T;
-            posb[j] = gt + min(eq_before, r) + min(lo, bs) + max(0, bs - hi);
-            quotab[j] = left >= own_eq ? kAllTies : max(left, 0);
-            if (bx == 0) {
-                count[bh] = lo + k + (n - hi);
-                if (threshold) threshold[bh] = (uint8_t)(k > 0 ? min(T, 255) : 0);   // saturates for b >= 256
-            }
+    }
+    __syncthreads();
+    if (tid < G) {
+        const int j = tid;
+        const int64_t bh = bh0 + j;
+        const int T = k > 0 ? thr[j] : kBinsW;                           // k = 0: nothing reaches the threshold
+        int r = 0, gt = 0, ge = 0, own_eq = 0;
+        if (k > 0) {
+            r = k - tot[j * kRow + T + 1];                               // slot b + 1 holds 0
+            ge = bef[j * kRow + T];                                      // #{score >= T} before this block
+            gt = bef[j * kRow + T + 1];
+            own_eq = own_ge_s[j] - own_gt_s[j];                          // #{score == T} inside this block
+        }
+        const int eq_before = ge - gt, left = r - eq_before;
+        const int bs = (int)min((int64_t)n, (int64_t)bx * block_tokens);   // always-kept tokens before this block
+        thr[j] = T;
+        posb[j] = gt + min(eq_before, r) + min(lo, bs) + max(0, bs - hi);
+        quotab[j] = left >= own_eq ? kAllTies : max(left, 0);
+        if (bx == 0) {
+            count[bh] = lo + k + (n - hi);
+            if (threshold) threshold[bh] = (uint8_t)(k > 0 ? min(T, 255) : 0);   // saturates for b >= 256
         }
     }
     __syncthreads();
 
     // ---- pass 1: score the unit once; masks per 64-token step and head, counts per wave
-    int T[G], cgt[G], ceq[G];
+    // A head whose ties all fit the quota at this block (or whose quota is used up) needs one mask only:
+    // "score >= T" (or "> T"); the tie mask is built for a head whose quota ends inside the block.
+    int T[G], take_from[G], cgt[G], ceq[G];
+    bool partial[G];
 #pragma unroll
-    for (int j = 0; j < G; ++j) { T[j] = uniform(thr[j]); cgt[j] = ceq[j] = 0; }
+    for (int j = 0; j < G; ++j) {
+        T[j] = uniform(thr[j]);
+        const int quota = uniform(quotab[j]);
+        take_from[j] = quota == kAllTies ? T[j] : T[j] + 1;
+        partial[j] = quota != kAllTies && quota != 0;
+        cgt[j] = ceq[j] = 0;
+    }
     for (int s0 = 0; s0 < n_steps; s0 += kDepth) {
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) {
@@ -272,8 +300,8 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
 #pragma unroll
                 for (int j = 0; j < G; ++j) {
                     const int sc = similarity<W>(kc, qs + j * W);
-                    const uint64_t g_mask = __ballot((scored && sc > T[j]) || (valid && !scored));   // kept tokens are always taken
-                    const uint64_t e_mask = __ballot(scored && sc == T[j]);
+                    const uint64_t g_mask = __builtin_amdgcn_ballot_w64((scored && sc >= take_from[j]) || (valid && !scored));   // kept tokens are always taken
+                    const uint64_t e_mask = partial[j] ? __builtin_amdgcn_ballot_w64(scored && sc == T[j]) : 0ull;
                     if (lane == 0) { m_gt[wave][s][j] = g_mask; m_eq[wave][s][j] = e_mask; }
                     cgt[j] += __popcll(g_mask);
                     ceq[j] += __popcll(e_mask);
