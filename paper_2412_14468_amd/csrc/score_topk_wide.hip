@@ -100,11 +100,15 @@ __global__ __launch_bounds__(kThreads) void score_hist_wide_kernel(KvView c, con
 
     unsigned* mine = hist + (lane & (kCopiesW - 1));
     const int s_end = min(t_end, hi);                               // scored tokens of this unit: [max(t_begin, lo), s_end)
-    auto fetch = [&](int t) {                                        // the code of token t, zeros outside the scored range
+    // The loads are unconditional (a token past the unit's end repeats the last one, and what is outside
+    // the scored range is masked where it is counted): loads under a per-lane condition would make the
+    // wave wait for all of them at every step instead of for the oldest only.
+    const bool active = t_begin < t_end;                             // uniform over the wave
+    auto fetch = [&](int t) {
         CodeWords<W> r;
 #pragma unroll
         for (int i = 0; i < W; ++i) r.w[i] = 0u;
-        if (t >= lo && t < s_end) r = load_code<PAGED, W>(c, b, kvh, t);
+        if (active) r = load_code<PAGED, W>(c, b, kvh, min(t, t_end - 1));
         return r;
     };
     constexpr int kDepth = depth_of(W);
@@ -116,7 +120,7 @@ __global__ __launch_bounds__(kThreads) void score_hist_wide_kernel(KvView c, con
         for (int d = 0; d < kDepth; ++d) {
             const int t = (int)base + d * kWave + lane;
             const CodeWords<W> cur = ring[d];
-            ring[d] = fetch(t + kDepth * kWave);                     // refill: kDepth steps ahead
+            ring[d] = load_code<PAGED, W>(c, b, kvh, min(t + kDepth * kWave, t_end - 1));   // refill: kDepth steps ahead
             if (t >= lo && t < s_end) {
 #pragma unroll
                 for (int j = 0; j < G; ++j)
@@ -189,11 +193,11 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
     // the first codes are requested before the tables are summed: they are not needed until the
     // threshold is known, and by then they have arrived
     const int n_steps = active ? (t_end - (int)t_begin + kWave - 1) / kWave : 0;
-    auto fetch = [&](int t) {                                        // the code of token t, zeros if it is not scored
+    auto fetch = [&](int t) {                                        // the code of token t (the unit's last one past its end)
         CodeWords<W> r;
 #pragma unroll
         for (int i = 0; i < W; ++i) r.w[i] = 0u;
-        if (active && t < t_end && t >= lo && t < hi) r = load_code<PAGED, W>(c, b, kvh, t);
+        if (active) r = load_code<PAGED, W>(c, b, kvh, min(t, t_end - 1));   // unconditional, see score_hist_wide_kernel
         return r;
     };
     constexpr int kDepth = depth_of(W);
@@ -278,6 +282,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
     // ---- pass 1: score the unit once; masks per 64-token step and head, counts per wave
     // A head whose ties all fit the quota at this block (or whose quota is used up) needs one mask only:
     // "score >= T" (or "> T"); the tie mask is built for a head whose quota ends inside the block.
+    // Steps past the unit's end (the step count is rounded up to the ring depth) leave empty masks.
     int T[G], take_from[G], cgt[G], ceq[G];
     bool partial[G];
 #pragma unroll
@@ -291,21 +296,19 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
     for (int s0 = 0; s0 < n_steps; s0 += kDepth) {
 #pragma unroll
         for (int d = 0; d < kDepth; ++d) {
-            const int s = s0 + d;
+            const int s = s0 + d;                                    // < kMaxSteps: units are whole multiples of the depth
             const int t = (int)t_begin + s * kWave + lane;
             const CodeWords<W> kc = ring[d];
-            ring[d] = fetch(t + kDepth * kWave);                     // refill: kDepth steps ahead
-            if (s < n_steps) {                                       // uniform over the wave
-                const bool valid = t < t_end, scored = valid && t >= lo && t < hi;
+            ring[d] = load_code<PAGED, W>(c, b, kvh, min(t + kDepth * kWave, t_end - 1));   // refill: kDepth steps ahead
+            const bool valid = t < t_end, scored = valid && t >= lo && t < hi;
 #pragma unroll
-                for (int j = 0; j < G; ++j) {
-                    const int sc = similarity<W>(kc, qs + j * W);
-                    const uint64_t g_mask = __builtin_amdgcn_ballot_w64((scored && sc >= take_from[j]) || (valid && !scored));   // kept tokens are always taken
-                    const uint64_t e_mask = partial[j] ? __builtin_amdgcn_ballot_w64(scored && sc == T[j]) : 0ull;
-                    if (lane == 0) { m_gt[wave][s][j] = g_mask; m_eq[wave][s][j] = e_mask; }
-                    cgt[j] += __popcll(g_mask);
-                    ceq[j] += __popcll(e_mask);
-                }
+            for (int j = 0; j < G; ++j) {
+                const int sc = similarity<W>(kc, qs + j * W);
+                const uint64_t g_mask = __builtin_amdgcn_ballot_w64((scored && sc >= take_from[j]) || (valid && !scored));   // kept tokens are always taken
+                const uint64_t e_mask = partial[j] ? __builtin_amdgcn_ballot_w64(scored && sc == T[j]) : 0ull;
+                if (lane == 0) { m_gt[wave][s][j] = g_mask; m_eq[wave][s][j] = e_mask; }
+                cgt[j] += __popcll(g_mask);
+                ceq[j] += __popcll(e_mask);
             }
         }
     }
@@ -323,7 +326,7 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
     const int tpl = unit_tokens >> 6;
     const int run0 = lane * tpl;                                     // first token of the run inside the unit
     const int rs = run0 >> 6, roff = run0 & 63;                      // its step and first bit there
-    const unsigned run_bits = rs < n_steps ? (1u << tpl) - 1u : 0u;  // steps past the unit's end hold stale masks
+    const unsigned run_bits = rs < n_steps ? (1u << tpl) - 1u : 0u;  // steps never scored hold stale masks
 #pragma unroll
     for (int j = 0; j < G; ++j) {
         const int gt_before = wave_sum_i32(lane < wave ? wgt[lane][j] : 0);
