@@ -145,7 +145,7 @@ int pick_unit_tokens(const hashattn_ctx* ctx, int batch, int max_seq_len, bool m
     // per wave in the select); blocks of 16 waves with units of 1024 measured faster there.
     int wpb = ha::kTopkWavesPerBlock;
     int unit = pick(wpb);
-    if (!wide && !mixed && lanes <= 16 && unit == kMaxUnit) {
+    if (!wide && !mixed && lanes <= 16 && unit == kMaxUnit && ctx->group <= 4) {   // 8 heads per group: a 16-wave block would spill
         wpb = 16;
         unit = pick(wpb);
     }

@@ -156,19 +156,17 @@ def test_c4_full_size_sampled_pairs_paged():
     run_sampled(cfg, W.BASE_SEED + 4004, [(longest, 2), (shortest, 5), (31, 0)])
 
 
-def test_topk_at_the_context_limit():
-    """SCORE + TOPK at the largest context a 32-bit context accepts (4 Mi tokens: 256 blocks of 8 units of
-    2048 tokens per sequence), uniform random codes, k = N / 32, one KV head with two query heads."""
+def codes_only_case(n, k, Hq, Hkv, seed):
+    """SCORE + TOPK on uniform random codes (K/V are not touched), every query head against the oracle."""
     import paper_2412_14468_amd as ha
     import gpu_util as gu
-    n, k, Hq = 4 * 1024 * 1024, 131072, 2
-    rng = np.random.default_rng(W.BASE_SEED + 4096)
-    codes = rng.integers(0, 2 ** 32, size=(1, 1, n), dtype=np.uint64).astype(np.uint32)
+    rng = np.random.default_rng(seed)
+    codes = rng.integers(0, 2 ** 32, size=(1, Hkv, n), dtype=np.uint64).astype(np.uint32)
     q_codes = rng.integers(0, 2 ** 32, size=(1, Hq), dtype=np.uint64).astype(np.uint32)
-    kz = torch.zeros((1, 1, 4, 128), dtype=torch.bfloat16, device=DEV)       # K/V are not touched by SCORE + TOPK
+    kz = torch.zeros((1, Hkv, 4, 128), dtype=torch.bfloat16, device=DEV)
     cache = ha.KvCache(kz, kz, gu.u32_dev(codes), torch.tensor([n], dtype=torch.int32, device=DEV), n)
     cache.c.n_max = n                                                         # the code store has n rows
-    ctx = ha.Context(Hq, 1, 1, n, k)
+    ctx = ha.Context(Hq, Hkv, 1, n, k)
     idx = torch.full((1, Hq, k), -7, dtype=torch.int32, device=DEV)
     count = torch.zeros((1, Hq), dtype=torch.int32, device=DEV)
     thr = torch.zeros((1, Hq), dtype=torch.uint8, device=DEV)
@@ -176,9 +174,22 @@ def test_topk_at_the_context_limit():
     torch.cuda.synchronize()
     idx_h = idx.cpu().numpy()
     for h in range(Hq):
-        sc = oracle.scores(int(q_codes[0, h]), codes[0, 0])
+        sc = oracle.scores(int(q_codes[0, h]), codes[0, h // (Hq // Hkv)])
         ref, rthr = oracle.topk_hist(sc, k)
         assert int(count[0, h]) == k and int(thr[0, h]) == rthr
         np.testing.assert_array_equal(idx_h[0, h], ref)
+
+
+def test_topk_at_the_context_limit():
+    """The largest context a 32-bit context accepts (4 Mi tokens: 256 blocks of 8 units of 2048 tokens per
+    sequence), k = N / 32, one KV head with two query heads."""
+    import paper_2412_14468_amd as ha
+    n = 4 * 1024 * 1024
+    codes_only_case(n, 131072, 2, 1, W.BASE_SEED + 4096)
     with pytest.raises(ha.HashAttnError, match="max_context"):
-        ha.Context(Hq, 1, 1, n + 1, k)
+        ha.Context(2, 1, 1, n + 1, 131072)
+
+
+def test_topk_groups_of_eight_at_512k():
+    """64 query heads on 8 KV heads at 512K tokens: units of 2048 tokens with eight heads per block."""
+    codes_only_case(524288, 16384, 64, 8, W.BASE_SEED + 4097)
