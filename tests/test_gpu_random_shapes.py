@@ -1,0 +1,51 @@
+"""Seeded random shapes for SCORE + TOPK (with and without the kept window) + GATHER-ATT through the C ABI:
+lengths (empty and one-token sequences included), budgets (zero and larger than the sequence included), group
+sizes, kept windows longer than the sequence, and code distributions with few distinct scores.  Every (sequence,
+head) is compared with the oracle: ids, counts and thresholds bit-exact, outputs within the tolerance."""
+import numpy as np
+import pytest
+
+from test_gpu_window import window_case
+
+pytestmark = pytest.mark.gpu
+
+
+def draw_case(rng):
+    tier = rng.integers(0, 3)
+    n = int((rng.integers(1, 300), rng.integers(1000, 6000), rng.integers(20000, 70000))[tier])
+    batch = int(rng.integers(1, 5))
+    hkv = int(rng.choice([1, 2]))
+    group = int(rng.choice([1, 2, 4, 8]))
+    lens = [int(x) for x in rng.integers(0, n + 1, size=batch)]
+    lens[int(rng.integers(0, batch))] = n                             # one sequence has the full length
+    if rng.random() < 0.3:
+        lens[int(rng.integers(0, batch))] = int(rng.choice([0, 1]))
+    k = int(rng.integers(1, max(2, n // 4)))
+    k_per_seq = None
+    if rng.random() < 0.5:
+        k_per_seq = [int(x) for x in rng.integers(0, k + 1, size=batch)]
+        k_per_seq[int(rng.integers(0, batch))] = k
+    n_sink, n_local = (0, 0) if rng.random() < 0.3 else (int(rng.integers(0, 200)), int(rng.integers(0, 200)))
+    kind = int(rng.integers(0, 3))
+    return dict(n=n, batch=batch, hkv=hkv, group=group, lens=lens, k=k, k_per_seq=k_per_seq, n_sink=n_sink,
+                n_local=n_local, kind=kind)
+
+
+def codes_of(kind, rng):
+    if kind == 0:                                                      # uniform codes
+        return lambda s: rng.integers(0, 2 ** 32, size=s, dtype=np.uint64).astype(np.uint32)
+    if kind == 1:                                                      # three distinct codes: long runs of ties
+        pool = rng.integers(0, 2 ** 32, size=3, dtype=np.uint64).astype(np.uint32)
+        return lambda s: pool[rng.integers(0, 3, size=s)]
+    return lambda s: (rng.integers(0, 2 ** 32, size=s, dtype=np.uint64).astype(np.uint32) & np.uint32(0x0000FFFF))  # scores in a narrow band
+
+
+@pytest.mark.parametrize("chunk", range(6))
+def test_random_shapes(chunk):
+    rng = np.random.default_rng(977 + chunk)
+    for i in range(10):
+        c = draw_case(rng)
+        print(f"case {chunk}.{i}: {c}", flush=True)
+        window_case(c["n"], c["k"], c["n_sink"], c["n_local"], codes_of(c["kind"], rng), batch=c["batch"],
+                    Hq=c["hkv"] * c["group"], Hkv=c["hkv"], lens=c["lens"], k_per_seq=c["k_per_seq"],
+                    check_out=c["n"] < 6000)
