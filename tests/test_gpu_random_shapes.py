@@ -49,3 +49,24 @@ def test_random_shapes(chunk):
         window_case(c["n"], c["k"], c["n_sink"], c["n_local"], codes_of(c["kind"], rng), batch=c["batch"],
                     Hq=c["hkv"] * c["group"], Hkv=c["hkv"], lens=c["lens"], k_per_seq=c["k_per_seq"],
                     check_out=c["n"] < 6000)
+
+
+@pytest.mark.parametrize("seed", range(5))
+def test_random_paged_whole_steps(seed):
+    """Paged caches with random page tables, mixed lengths and a budget per sequence: the whole step
+    (key codes, query codes, SCORE + TOPK, GATHER-ATT), staged against the oracle."""
+    import workloads as W
+    import gpu_util
+    import test_gpu_parity
+    test_gpu_parity.gu = gpu_util                      # that module binds it in a fixture of its own
+    run_whole_step = test_gpu_parity.run_whole_step
+    rng = np.random.default_rng(4242 + seed)
+    lo = int(rng.integers(1, 400))
+    hi = int(rng.integers(lo + 16, 9000))
+    batch = int(rng.integers(1, 7))
+    heads = [(32, 8), (8, 8), (16, 2), (8, 1)][int(rng.integers(0, 4))]
+    cfg = W.scaled(W.c4(batch=batch, lo=lo, hi=hi), planted=int(rng.integers(0, 6)), n_q_heads=heads[0],
+                   n_kv_heads=heads[1], k_divisor=int(rng.choice([4, 16, 32])))
+    print(f"paged case {seed}: batch={batch} lengths in [{lo}, {hi}] heads={heads} k=N/{cfg.k_divisor}", flush=True)
+    L = W.make_layer(cfg, seed=500 + seed)
+    run_whole_step(L)
