@@ -324,9 +324,18 @@ def main():
             res = oracle.decode_step(phi_q, phi_kv, ocache, L0.q, L0.k_per_seq, scale, n_sink=args.sink, n_local=args.local)
             times.append(time.perf_counter() - t0)
         cpu_s = float(np.median(times))
+        cores = oracle.num_threads()
+        oracle.set_threads(1)                                        # the same step on one host thread, for reference
+        one = []
+        for _ in range(3):
+            t0 = time.perf_counter()
+            oracle.decode_step(phi_q, phi_kv, ocache, L0.q, L0.k_per_seq, scale, n_sink=args.sink, n_local=args.local)
+            one.append(time.perf_counter() - t0)
+        oracle.set_threads(cores)
         cpu = {"value": round(alg_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "us_per_layer_step": round(cpu_s * 1e6, 1),
-               "cores": oracle.num_threads(), "kind": "oracle",
-               "sample": f"whole {cfg.name} layer-step (all {B * Hq} (sequence, head) pairs), median of {len(times)} runs"}
+               "cores": cores, "kind": "oracle",
+               "sample": f"whole {cfg.name} layer-step (all {B * Hq} (sequence, head) pairs), median of {len(times)} runs",
+               "one_thread_us_per_layer_step": round(float(np.median(one)) * 1e6, 1)}
         # parity of ring layer 0 against the oracle, staged as in tests/: the GPU's own codes are compared
         # bit by bit (they may differ where the pre-sign activation is within rounding of 0), then SCORE +
         # TOPK + GATHER-ATT run on the oracle's codes, where index sets must be identical

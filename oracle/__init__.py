@@ -33,6 +33,8 @@ def lib():
     if _lib is None:
         L = C.CDLL(_build(force=False))
         L.ha_oracle_num_threads.restype = C.c_int
+        L.ha_oracle_set_threads.restype = None
+        L.ha_oracle_set_threads.argtypes = [C.c_int]
         L.ha_oracle_encode_vec.restype = C.c_uint32
         L.ha_oracle_encode_vec.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         L.ha_oracle_encode_query.restype = None
@@ -97,6 +99,11 @@ def lib():
 
 def num_threads() -> int:
     return int(lib().ha_oracle_num_threads())
+
+
+def set_threads(n: int) -> None:
+    """Threads for the (sequence, head) loops from now on (used for timing; results do not depend on it)."""
+    lib().ha_oracle_set_threads(int(n))
 
 
 def _ptr(a: Optional[np.ndarray]):

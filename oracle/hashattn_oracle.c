@@ -77,6 +77,16 @@ static int64_t row_of(const ha_cache* c, int b, int h, int64_t t)
     return (page * c->n_kv_heads + h) * c->page_size + t % c->page_size;
 }
 
+/* Threads the (sequence, head) loops may use from now on (timing only: results do not depend on it). */
+void ha_oracle_set_threads(int n)
+{
+#ifdef _OPENMP
+    if (n >= 1) omp_set_num_threads(n);
+#else
+    (void)n;
+#endif
+}
+
 int ha_oracle_num_threads(void)
 {
 #ifdef _OPENMP
