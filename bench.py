@@ -3,8 +3,9 @@
 
 A step is one pass of the whole hot path over one layer: encode query -> SCORE + TOPK ->
 GATHER-ATT (preceded by the one-token append where the workload has one).  Steps walk a ring of
-distinct layers (own K/V, codes and mapping weights) larger than the 256 MB Infinity Cache, so a
-step reads its codes and rows from HBM as a 32-layer decode does.  A whole sweep over the ring is
+distinct layers (own K/V, codes and mapping weights) whose codes and weights alone exceed the 256 MB
+Infinity Cache, so a step reads everything from HBM, as a decode that streams the model's weights
+between two visits of a layer does.  A whole sweep over the ring is
 captured in one HIP graph and replayed, which removes the host's launch cost from the step as a
 serving loop would.
 
@@ -50,14 +51,18 @@ def parse_args():
     return ap.parse_args()
 
 
-# workload name -> (config factory, ring length).  The ring is sized past the 256 MB Infinity Cache.
+# workload name -> (config factory, ring length): the steps walk a ring of distinct layers whose key codes and mapping weights
+# alone exceed the 256 MB Infinity Cache (the K/V rows are loaded with the non-temporal hint and do not
+# displace them), so that every read of a step comes from HBM, as it does in a model that streams its
+# weights between two visits of a layer.  Measured: C1 takes 23.9 us per step on a ring of 32 layers
+# (codes and weights stay cached) and 25.7 us from 128 layers on.
 WORKLOADS = {
-    "C1": (lambda W: W.c1(), 32),
-    "C1-128K": (lambda W: W.scaled(W.c1(context=131072), name="C1-128K"), 8),
-    "C2": (lambda W: W.c2(), 2),
-    "C3": (lambda W: W.c3(), 4),
-    "C3-16x": (lambda W: W.scaled(W.c3(k=32768), name="C3-16x"), 4),
-    "C4": (lambda W: W.c4(), 2),
+    "C1": (lambda W: W.c1(), 128),
+    "C1-128K": (lambda W: W.scaled(W.c1(context=131072), name="C1-128K"), 64),
+    "C2": (lambda W: W.c2(), 5),
+    "C3": (lambda W: W.c3(), 20),
+    "C3-16x": (lambda W: W.scaled(W.c3(k=32768), name="C3-16x"), 20),
+    "C4": (lambda W: W.c4(), 7),
 }
 
 
