@@ -247,7 +247,7 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
         hashattn_destroy(ctx);
         return fail(nullptr, HASHATTN_HIP_ERROR, "create: raising the LDS limit of the key encoder: %s", hipGetErrorString(e));
     }
-    if ((e = ha::setup_score_topk(group)) != hipSuccess) {
+    if ((e = cfg->bits == ha::kBits ? ha::setup_score_topk(group) : ha::setup_score_topk_wide(group, cfg->bits / ha::kBits)) != hipSuccess) {
         hashattn_destroy(ctx);
         return fail(nullptr, HASHATTN_HIP_ERROR, "create: raising the LDS limit of the TOPK kernels: %s", hipGetErrorString(e));
     }

@@ -63,6 +63,7 @@ hipError_t launch_score_topk(const KvView& kv, bool paged, int group, const Topk
 
 // Signatures of 32 * words bits (words = 2, 4, 8, 16): codes and q_codes carry a trailing axis of
 // `words`, blk_cum rows have 32 * words + 2 ints, unit_tokens is at most 1024.
+hipError_t setup_score_topk_wide(int group, int words);
 hipError_t launch_score_topk_wide(const KvView& kv, bool paged, int group, int words, const TopkCall& call,
                                   int unit_tokens, const TopkScratch& sc, hipStream_t stream);
 

@@ -17,6 +17,8 @@
 //     of those masks, and ranks and stores the ids as the 32-bit select does (ties in token order
 //     against the wave's share of the quota).
 // Units are 256, 512 or 1024 tokens (16 steps of masks per wave at most).
+// For W = 2 and 4 with up to eight 16-byte loads per lane the select is the 32-bit one carried over
+// (topk_select_runs_kernel, further down); the step-mask select serves the rest.
 #include "kernels.hpp"
 
 namespace ha {
@@ -349,15 +351,277 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
     }
 }
 
-template <int G, bool PAGED, int W>
-hipError_t launch_w(const KvView& kv, const TopkCall& a, int unit_tokens, const TopkScratch& sc, hipStream_t stream)
+// ---------------------------------------------------------------------------------------------
+// 64- and 128-bit signatures (W = 2, 4) with units of up to 8 x 16 bytes per lane: the select of the
+// 32-bit path carried over.  The wave loads its unit coalesced, transposes it through LDS so that a
+// lane holds kTpl consecutive tokens (W words each), and builds a lane's take mask with 2 W + 1
+// instructions per token and head (xor and a counting add per word, one funnel shift for the top bit
+// of "distance + bias"): no wave ballots, no masks in LDS.  NIT: 16-byte loads per lane.
+template <int TPL, int W>
+__device__ __forceinline__ unsigned within_mask_words(const uint32_t (&w)[TPL * W], const uint32_t (&q)[W], int lim)
 {
+    const unsigned bias = 0x7fffffffu - (unsigned)lim;          // top bit of distance + bias: distance > lim
+    unsigned m = 0;
+#pragma unroll
+    for (int p = TPL - 1; p >= 0; --p) {
+        unsigned d = bias;
+#pragma unroll
+        for (int i = 0; i < W; ++i)                              // the count instruction adds its second operand
+            asm("v_xor_b32 %0, %2, %1\n\tv_bcnt_u32_b32 %0, %0, %3" : "=&v"(d) : "v"(w[p * W + i]), "s"(q[i]), "v"(d));
+        m = __builtin_amdgcn_alignbit(m, d, 31);                 // (m << 1) | top bit of d
+    }
+    return ~m;
+}
+
+template <int TPL, int W>
+__device__ __forceinline__ unsigned equal_mask_words(const uint32_t (&w)[TPL * W], const uint32_t (&q)[W], int dist)
+{
+    unsigned m = 0;
+#pragma unroll
+    for (int p = TPL - 1; p >= 0; --p) {
+        int d = 0;
+#pragma unroll
+        for (int i = 0; i < W; ++i) d += __popc(w[p * W + i] ^ q[i]);
+        m = (m << 1) | (unsigned)(d == dist);
+    }
+    return m;
+}
+
+template <int G, bool PAGED, int W, int NIT>
+__global__ __launch_bounds__(kThreads) void topk_select_runs_kernel(KvView c, const uint32_t* __restrict__ q_codes,
+                                                                    const int32_t* __restrict__ k_per_seq, int k_max,
+                                                                    int n_sink, int n_local, int pitch, int n_q_heads,
+                                                                    int n_cap, int blocks_pitch,
+                                                                    const int32_t* __restrict__ blk_cum,
+                                                                    int32_t* __restrict__ idx, int32_t* __restrict__ count,
+                                                                    uint8_t* __restrict__ threshold)
+{
+    constexpr int kBinsW = bins_of(W), kRow = kBinsW + 1, kBitsW = 32 * W;
+    constexpr int kPieceTokens = 4 / W;                              // tokens in 16 bytes
+    constexpr int kUnit = NIT * kWave * kPieceTokens;                // tokens per wave: 256 NIT / W
+    constexpr int kTpl = kUnit / kWave;                              // tokens per lane after the transposition
+    static_assert(kTpl >= 4 && kTpl <= 16, "a lane's take mask must fit the emit helpers");
+    extern __shared__ uint4 stage_all[];                             // 64 NIT pieces per wave
+    __shared__ int tot[G * kRow], bef[G * kRow];
+    __shared__ int thr[G], posb[G], quotab[G], own_ge_s[G], own_gt_s[G];
+    __shared__ int wgt[kWpb][G], weq[kWpb][G];
+    __shared__ uint32_t qs[G * W];
+    const int tid = threadIdx.x, wave = uniform(tid >> 6), lane = tid & 63;
+    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int bx = rotated_block(blockIdx.x, kvh + b, gridDim.x);
+    const int64_t bh0 = (int64_t)b * n_q_heads + kvh * G;
+    const int n = min(c.seq_lens[b], n_cap);
+    const int k_raw = k_per_seq ? k_per_seq[b] : k_max;
+    const int lo = min(n_sink, n), hi = max(lo, n - n_local);
+    const int k = max(0, min(k_raw, min(k_max, hi - lo)));
+    const bool nothing = k == 0 && lo == 0 && hi == n;
+    constexpr int block_tokens = kWpb * kUnit;
+    if (bx > 0 && ((int64_t)bx * block_tokens >= n || nothing)) return;   // block 0 reports the counts
+    const int n_blocks = (n + block_tokens - 1) / block_tokens;
+    const int64_t t_begin = ((int64_t)bx * kWpb + wave) * kUnit;
+    const bool active = t_begin < n && !nothing;
+    const int t_end = (int)min((int64_t)n, t_begin + kUnit);
+
+    // the unit's codes, coalesced: piece it * 64 + lane holds tokens t_begin + piece * kPieceTokens ..; a
+    // piece past the end repeats the last one (masked below), so the loads are unconditional
+    uint4 cw[NIT];
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) cw[it] = make_uint4(0u, 0u, 0u, 0u);
+    if (active) {
+        const int last = (t_end - 1) & ~(kPieceTokens - 1);
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) {
+            const int t = min((int)t_begin + (it * kWave + lane) * kPieceTokens, last);
+            cw[it] = *reinterpret_cast<const uint4*>(c.codes + row_of<PAGED>(c, b, kvh, t) * W);
+        }
+    }
+
+    if (tid < G) { thr[tid] = -1; own_ge_s[tid] = own_gt_s[tid] = 0; }
+    if (tid < G * W) qs[tid] = q_codes[bh0 * W + tid];
+    // cumulative counts from the per-block rows in one trip to memory (see topk_select_wide_kernel)
+    constexpr int kIter = (G * kRow + kThreads - 1) / kThreads;
+    int own_r[kIter];
+#pragma unroll
+    for (int it = 0; it < kIter; ++it) {
+        const int i = tid + it * kThreads;
+        own_r[it] = 0;
+        if (i < G * kRow) {
+            const int j = i / kRow, col = i - j * kRow;
+            const int32_t* p = blk_cum + (bh0 + j) * blocks_pitch * kRow + col;
+            int v = 0, vb = 0;
+            for (int blk0 = 0; blk0 < n_blocks; blk0 += 16) {
+                int part[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) part[u] = blk0 + u < n_blocks ? p[(int64_t)(blk0 + u) * kRow] : 0;
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    v += part[u];
+                    if (blk0 + u < bx) vb += part[u];
+                    if (blk0 + u == bx) own_r[it] = part[u];
+                }
+            }
+            tot[i] = v;
+            bef[i] = vb;
+        }
+    }
+    __syncthreads();
+    if (k > 0) {
+        for (int i = tid; i < G * kBinsW; i += kThreads) {
+            const int j = i / kBinsW, sc = i - j * kBinsW;
+            if (tot[j * kRow + sc] >= k) atomicMax(&thr[j], sc);
+        }
+    }
+    __syncthreads();
+    if (k > 0) {
+#pragma unroll
+        for (int it = 0; it < kIter; ++it) {
+            const int i = tid + it * kThreads;
+            if (i < G * kRow) {
+                const int j = i / kRow, col = i - j * kRow;
+                if (col == thr[j]) own_ge_s[j] = own_r[it];
+                if (col == thr[j] + 1) own_gt_s[j] = own_r[it];
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < G) {
+        const int j = tid;
+        const int64_t bh = bh0 + j;
+        const int T = k > 0 ? thr[j] : kBinsW;
+        int r = 0, gt = 0, ge = 0, own_eq = 0;
+        if (k > 0) {
+            r = k - tot[j * kRow + T + 1];
+            ge = bef[j * kRow + T];
+            gt = bef[j * kRow + T + 1];
+            own_eq = own_ge_s[j] - own_gt_s[j];
+        }
+        const int eq_before = ge - gt, left = r - eq_before;
+        const int bs = (int)min((int64_t)n, (int64_t)bx * block_tokens);
+        thr[j] = T;
+        posb[j] = gt + min(eq_before, r) + min(lo, bs) + max(0, bs - hi);
+        quotab[j] = left >= own_eq ? kAllTies : max(left, 0);
+        if (bx == 0) {
+            count[bh] = lo + k + (n - hi);
+            if (threshold) threshold[bh] = (uint8_t)(k > 0 ? min(T, 255) : 0);
+        }
+    }
+    __syncthreads();
+
+    // ---- lane runs and masks
+    unsigned sel[G], tie[G];
+    int quota[G];
+#pragma unroll
+    for (int j = 0; j < G; ++j) { sel[j] = tie[j] = 0u; quota[j] = uniform(quotab[j]); }
+    if (active) {
+        uint32_t w[kTpl * W];
+        uint4* stage = stage_all + wave * (kWave * NIT);
+#pragma unroll
+        for (int it = 0; it < NIT; ++it) stage[it * kWave + lane] = cw[it];     // piece p belongs to lane p / NIT
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+        for (int i = 0; i < NIT; ++i) {
+            const uint4 x = stage[lane * NIT + i];
+            w[4 * i] = x.x; w[4 * i + 1] = x.y; w[4 * i + 2] = x.z; w[4 * i + 3] = x.w;
+        }
+        const int first = (int)t_begin + lane * kTpl;                              // first token of this lane's run
+        auto below = [&](int t) { return (1u << max(0, min(t - first, kTpl))) - 1u; };   // bits of tokens < t
+        const unsigned valid = below(t_end);
+        const unsigned scored = below(hi) & ~below(lo) & valid;
+        const unsigned kept = valid & ~scored;
+#pragma unroll
+        for (int j = 0; j < G; ++j) {
+            uint32_t q[W];
+#pragma unroll
+            for (int i = 0; i < W; ++i) q[i] = (uint32_t)uniform((int)qs[j * W + i]);
+            const int T = uniform(thr[j]);
+            const int lim = quota[j] == kAllTies ? kBitsW - T : kBitsW - T - 1;   // bound on the Hamming distance
+            sel[j] = (within_mask_words<kTpl, W>(w, q, lim) & scored) | kept;
+            if (quota[j] != kAllTies && quota[j] != 0) tie[j] = equal_mask_words<kTpl, W>(w, q, kBitsW - T) & scored;
+        }
+    }
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        const int cs = wave_sum_i32(__popc(sel[j]));
+        const int es = wave_sum_i32(__popc(tie[j]));
+        if (lane == 0) { wgt[wave][j] = cs; weq[wave][j] = es; }
+    }
+    __syncthreads();
+    if (!active) return;
+
+    // ---- ranks and ids (ties in token order while the wave's share of the quota lasts)
+    const int first = (int)t_begin + lane * kTpl;
+#pragma unroll
+    for (int j = 0; j < G; ++j) {
+        const int gt_before = wave_sum_i32(lane < wave ? wgt[lane][j] : 0);
+        const int eq_before = wave_sum_i32(lane < wave ? weq[lane][j] : 0);
+        const int quota_w = quota[j] == kAllTies ? kAllTies : max(0, quota[j] - eq_before);
+        const int start = uniform(posb[j]) + gt_before + min(eq_before, quota[j] == kAllTies ? 0 : quota[j]);
+        unsigned take = sel[j];
+        if (quota_w != kAllTies && quota_w > 0) {
+            const int mine = __popc(tie[j]);
+            const int incl = wave_incl_scan_i32(mine);
+            take |= lowest_bits(tie[j], max(0, min(mine, quota_w - (incl - mine))));
+        }
+        const int cnt = __popc(take);
+        const int incl = wave_incl_scan_i32(cnt);
+        emit_ids(take, start + incl - cnt, first, pitch, idx + (bh0 + j) * pitch);
+    }
+}
+
+// The lane-run select for W = 2, 4: launch (or, with setup_only, raise the dynamic LDS limit of) the variant
+// with NIT 16-byte loads per lane.
+template <int G, bool PAGED, int W, int NIT>
+hipError_t select_runs(bool setup_only, const KvView& kv, const TopkCall& a, const TopkScratch& sc, dim3 grid,
+                       hipStream_t stream)
+{
+    constexpr int lds = kWpb * kWave * NIT * (int)sizeof(uint4);
+    if (setup_only)
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_select_runs_kernel<G, PAGED, W, NIT>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    topk_select_runs_kernel<G, PAGED, W, NIT><<<grid, dim3(kThreads), lds, stream>>>(
+        kv, a.q_codes, a.k_per_seq, a.k_max, a.n_sink, a.n_local, a.k_max + a.n_sink + a.n_local, a.n_q_heads,
+        a.max_seq_len, sc.blocks_pitch, sc.blk_cum, a.idx, a.count, a.threshold);
+    return hipSuccess;
+}
+
+// true if a lane-run variant exists for (W, unit_tokens): up to eight 16-byte loads per lane
+template <int G, bool PAGED, int W>
+bool select_runs_by_unit(bool setup_only, int unit_tokens, const KvView& kv, const TopkCall& a, const TopkScratch& sc,
+                         dim3 grid, hipStream_t stream, hipError_t* e)
+{
+    *e = hipSuccess;
+    if constexpr (W == 2 || W == 4) {
+        switch (unit_tokens * W / 256) {
+        case 2: if constexpr (W == 2) { *e = select_runs<G, PAGED, W, 2>(setup_only, kv, a, sc, grid, stream); return true; } break;
+        case 4: *e = select_runs<G, PAGED, W, 4>(setup_only, kv, a, sc, grid, stream); return true;
+        case 8: *e = select_runs<G, PAGED, W, 8>(setup_only, kv, a, sc, grid, stream); return true;
+        default: break;
+        }
+    }
+    return false;
+}
+
+template <int G, bool PAGED, int W>
+hipError_t launch_w(bool setup_only, const KvView& kv, const TopkCall& a, int unit_tokens, const TopkScratch& sc,
+                    hipStream_t stream)
+{
+    if (setup_only) {
+        hipError_t e = hipSuccess;
+        for (int unit = 256; unit <= 1024; unit *= 2)
+            if (select_runs_by_unit<G, PAGED, W>(true, unit, kv, a, sc, dim3(1), stream, &e) && e != hipSuccess) return e;
+        return hipSuccess;
+    }
     const int64_t block_tokens = (int64_t)kWpb * unit_tokens;
     int n_blocks = (int)((a.max_seq_len + block_tokens - 1) / block_tokens);
     if (n_blocks < 1) n_blocks = 1;
     const dim3 grid(n_blocks, kv.n_kv_heads, a.batch), block(kThreads);
     score_hist_wide_kernel<G, PAGED, W><<<grid, block, 0, stream>>>(kv, a.q_codes, a.n_q_heads, a.max_seq_len, unit_tokens,
                                                                    a.n_sink, a.n_local, sc.blocks_pitch, sc.blk_cum);
+    hipError_t e = hipSuccess;
+    if (select_runs_by_unit<G, PAGED, W>(false, unit_tokens, kv, a, sc, grid, stream, &e))
+        return e != hipSuccess ? e : hipGetLastError();
     topk_select_wide_kernel<G, PAGED, W><<<grid, block, 0, stream>>>(
         kv, a.q_codes, a.k_per_seq, a.k_max, a.n_sink, a.n_local, a.k_max + a.n_sink + a.n_local, a.n_q_heads,
         a.max_seq_len, unit_tokens, sc.blocks_pitch, sc.blk_cum, a.idx, a.count, a.threshold);
@@ -365,40 +629,57 @@ hipError_t launch_w(const KvView& kv, const TopkCall& a, int unit_tokens, const 
 }
 
 template <int G, bool PAGED>
-hipError_t launch_words(int words, const KvView& kv, const TopkCall& a, int unit_tokens, const TopkScratch& sc,
-                        hipStream_t stream)
+hipError_t launch_words(bool setup_only, int words, const KvView& kv, const TopkCall& a, int unit_tokens,
+                        const TopkScratch& sc, hipStream_t stream)
 {
     switch (words) {
-    case 2: return launch_w<G, PAGED, 2>(kv, a, unit_tokens, sc, stream);
-    case 4: return launch_w<G, PAGED, 4>(kv, a, unit_tokens, sc, stream);
-    case 8: return launch_w<G, PAGED, 8>(kv, a, unit_tokens, sc, stream);
-    case 16: return launch_w<G, PAGED, 16>(kv, a, unit_tokens, sc, stream);
+    case 2: return launch_w<G, PAGED, 2>(setup_only, kv, a, unit_tokens, sc, stream);
+    case 4: return launch_w<G, PAGED, 4>(setup_only, kv, a, unit_tokens, sc, stream);
+    case 8: return launch_w<G, PAGED, 8>(setup_only, kv, a, unit_tokens, sc, stream);
+    case 16: return launch_w<G, PAGED, 16>(setup_only, kv, a, unit_tokens, sc, stream);
     default: return hipErrorInvalidValue;
     }
 }
 
 template <int G>
-hipError_t launch_group(bool paged, int words, const KvView& kv, const TopkCall& a, int unit_tokens,
+hipError_t launch_group(bool setup_only, bool paged, int words, const KvView& kv, const TopkCall& a, int unit_tokens,
                         const TopkScratch& sc, hipStream_t stream)
 {
-    return paged ? launch_words<G, true>(words, kv, a, unit_tokens, sc, stream)
-                 : launch_words<G, false>(words, kv, a, unit_tokens, sc, stream);
+    if (setup_only) {
+        if (hipError_t e = launch_words<G, false>(true, words, kv, a, unit_tokens, sc, stream); e != hipSuccess) return e;
+        return launch_words<G, true>(true, words, kv, a, unit_tokens, sc, stream);
+    }
+    return paged ? launch_words<G, true>(false, words, kv, a, unit_tokens, sc, stream)
+                 : launch_words<G, false>(false, words, kv, a, unit_tokens, sc, stream);
+}
+
+hipError_t dispatch_wide(bool setup_only, bool paged, int group, int words, const KvView& kv, const TopkCall& call,
+                         int unit_tokens, const TopkScratch& sc, hipStream_t stream)
+{
+    switch (group) {
+    case 1: return launch_group<1>(setup_only, paged, words, kv, call, unit_tokens, sc, stream);
+    case 2: return launch_group<2>(setup_only, paged, words, kv, call, unit_tokens, sc, stream);
+    case 4: return launch_group<4>(setup_only, paged, words, kv, call, unit_tokens, sc, stream);
+    case 8: return launch_group<8>(setup_only, paged, words, kv, call, unit_tokens, sc, stream);
+    default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace
+
+// Raises the dynamic LDS limit of the lane-run select kernels of this group size and width (their staging
+// area reaches 64 KiB); called once when a context is created, never on the launch path.
+hipError_t setup_score_topk_wide(int group, int words)
+{
+    return dispatch_wide(true, false, group, words, KvView{}, TopkCall{}, 0, TopkScratch{}, nullptr);
+}
 
 // unit_tokens: 256, 512 or 1024
 hipError_t launch_score_topk_wide(const KvView& kv, bool paged, int group, int words, const TopkCall& call,
                                   int unit_tokens, const TopkScratch& sc, hipStream_t stream)
 {
     if (unit_tokens > kMaxSteps * kWave) return hipErrorInvalidValue;
-    switch (group) {
-    case 1: return launch_group<1>(paged, words, kv, call, unit_tokens, sc, stream);
-    case 2: return launch_group<2>(paged, words, kv, call, unit_tokens, sc, stream);
-    case 4: return launch_group<4>(paged, words, kv, call, unit_tokens, sc, stream);
-    case 8: return launch_group<8>(paged, words, kv, call, unit_tokens, sc, stream);
-    default: return hipErrorInvalidValue;
-    }
+    return dispatch_wide(false, paged, group, words, kv, call, unit_tokens, sc, stream);
 }
 
 }  // namespace ha

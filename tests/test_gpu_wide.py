@@ -77,7 +77,7 @@ def test_topk_wide_random_codes(words):
     topk_wide_case(words, 1, 1)
 
 
-@pytest.mark.parametrize("words", [2, 16])
+@pytest.mark.parametrize("words", [2, 4, 16])
 def test_topk_wide_heavy_ties_and_ragged_batches(words):
     def few_codes(rng, shape):
         base = rand_words(rng, (3, shape[-1]))
@@ -99,6 +99,8 @@ def test_topk_wide_group_sizes_and_paged(words, Hq, Hkv):
 def test_topk_wide_long_context_units_of_512_and_1024():
     topk_wide_case(4, 600000, 4000, Hq=2, Hkv=1, n_sink=5000, n_local=9000)        # pitch forces units of 512
     topk_wide_case(2, 40000, 1000, batch=64, Hq=2, Hkv=1)                           # many lanes: units of 1024
+    topk_wide_case(2, 600001, 3000, Hq=4, Hkv=1, n_sink=7, n_local=1000)            # 64 bits in units of 512
+    topk_wide_case(4, 30000, 900, batch=40, Hq=2, Hkv=1)                            # 128 bits in units of 1024 (step-mask select)
 
 
 @pytest.mark.parametrize("bits,dims", [(64, (128, 128, 64)), (128, (128, 128)), (256, (128, 64, 128, 256)),
