@@ -161,6 +161,91 @@ __global__ __launch_bounds__(kThreads) void score_hist_wide_kernel(KvView c, con
     }
 }
 
+// Selection parameters of a block, per head, from the per-block rows of cumulative counts (one trip to
+// memory, one thread per (head, score)): the threshold thr[j] (largest score s with C(s) >= k), the
+// block's first output slot posb[j] and its tie quota quotab[j]; block 0 also stores count and
+// threshold.  tot, bef: [G][b + 2] ints of LDS; the others [G].  Every thread of the block calls it.
+template <int G, int W>
+__device__ __forceinline__ void block_selection(const int32_t* __restrict__ blk_cum, int64_t bh0, int blocks_pitch,
+                                                int n_blocks, int bx, int block_tokens, int n, int lo, int hi, int k,
+                                                int* tot, int* bef, int* thr, int* posb, int* quotab, int* own_ge_s,
+                                                int* own_gt_s, int32_t* __restrict__ count,
+                                                uint8_t* __restrict__ threshold)
+{
+    constexpr int kBinsW = bins_of(W), kRow = kBinsW + 1;
+    const int tid = threadIdx.x;
+    if (tid < G) { thr[tid] = -1; own_ge_s[tid] = own_gt_s[tid] = 0; }
+    // sums over the whole sequence (tot), over the blocks before this one (bef), and this block's own row
+    // (kept in registers until the threshold says which two of its entries matter)
+    constexpr int kIter = (G * kRow + kThreads - 1) / kThreads;
+    int own_r[kIter];
+#pragma unroll
+    for (int it = 0; it < kIter; ++it) {
+        const int i = tid + it * kThreads;
+        own_r[it] = 0;
+        if (i < G * kRow) {
+            const int j = i / kRow, col = i - j * kRow;
+            const int32_t* p = blk_cum + (bh0 + j) * blocks_pitch * kRow + col;
+            int v = 0, vb = 0;
+            for (int blk0 = 0; blk0 < n_blocks; blk0 += 16) {           // sixteen independent loads per trip to memory
+                int part[16];
+#pragma unroll
+                for (int u = 0; u < 16; ++u) part[u] = blk0 + u < n_blocks ? p[(int64_t)(blk0 + u) * kRow] : 0;
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    v += part[u];
+                    if (blk0 + u < bx) vb += part[u];
+                    if (blk0 + u == bx) own_r[it] = part[u];
+                }
+            }
+            tot[i] = v;
+            bef[i] = vb;
+        }
+    }
+    __syncthreads();
+    if (k > 0) {                                                         // C(0) = number of scored tokens >= k
+        for (int i = tid; i < G * kBinsW; i += kThreads) {
+            const int j = i / kBinsW, sc = i - j * kBinsW;
+            if (tot[j * kRow + sc] >= k) atomicMax(&thr[j], sc);
+        }
+    }
+    __syncthreads();
+    if (k > 0) {
+#pragma unroll
+        for (int it = 0; it < kIter; ++it) {
+            const int i = tid + it * kThreads;
+            if (i < G * kRow) {
+                const int j = i / kRow, col = i - j * kRow;
+                if (col == thr[j]) own_ge_s[j] = own_r[it];
+                if (col == thr[j] + 1) own_gt_s[j] = own_r[it];
+            }
+        }
+    }
+    __syncthreads();
+    if (tid < G) {
+        const int j = tid;
+        const int64_t bh = bh0 + j;
+        const int T = k > 0 ? thr[j] : kBinsW;                           // k = 0: nothing reaches the threshold
+        int r = 0, gt = 0, ge = 0, own_eq = 0;
+        if (k > 0) {
+            r = k - tot[j * kRow + T + 1];                               // slot b + 1 holds 0
+            ge = bef[j * kRow + T];                                      // #{score >= T} before this block
+            gt = bef[j * kRow + T + 1];
+            own_eq = own_ge_s[j] - own_gt_s[j];                          // #{score == T} inside this block
+        }
+        const int eq_before = ge - gt, left = r - eq_before;
+        const int bs = (int)min((int64_t)n, (int64_t)bx * block_tokens);   // always-kept tokens before this block
+        thr[j] = T;
+        posb[j] = gt + min(eq_before, r) + min(lo, bs) + max(0, bs - hi);
+        quotab[j] = left >= own_eq ? kAllTies : max(left, 0);
+        if (bx == 0) {
+            count[bh] = lo + k + (n - hi);
+            if (threshold) threshold[bh] = (uint8_t)(k > 0 ? min(T, 255) : 0);   // saturates for b >= 256
+        }
+    }
+    __syncthreads();
+}
+
 template <int G, bool PAGED, int W>
 __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, const uint32_t* __restrict__ q_codes,
                                                                     const int32_t* __restrict__ k_per_seq, int k_max,
@@ -207,79 +292,9 @@ __global__ __launch_bounds__(kThreads) void topk_select_wide_kernel(KvView c, co
 #pragma unroll
     for (int d = 0; d < kDepth; ++d) ring[d] = fetch((int)t_begin + d * kWave + lane);
 
-    if (tid < G) { thr[tid] = -1; own_ge_s[tid] = own_gt_s[tid] = 0; }
     if (tid < G * W) qs[tid] = q_codes[bh0 * W + tid];
-    // Cumulative counts from the per-block rows in one trip to memory, one thread per (head, score):
-    // over the whole sequence (tot), over the blocks before this one (bef), and this block's own row
-    // (kept in registers until the threshold says which two of its entries matter).
-    constexpr int kIter = (G * kRow + kThreads - 1) / kThreads;
-    int own_r[kIter];
-#pragma unroll
-    for (int it = 0; it < kIter; ++it) {
-        const int i = tid + it * kThreads;
-        own_r[it] = 0;
-        if (i < G * kRow) {
-            const int j = i / kRow, col = i - j * kRow;
-            const int32_t* p = blk_cum + (bh0 + j) * blocks_pitch * kRow + col;
-            int v = 0, vb = 0;
-            for (int blk0 = 0; blk0 < n_blocks; blk0 += 16) {           // sixteen independent loads per trip to memory
-                int part[16];
-#pragma unroll
-                for (int u = 0; u < 16; ++u) part[u] = blk0 + u < n_blocks ? p[(int64_t)(blk0 + u) * kRow] : 0;
-#pragma unroll
-                for (int u = 0; u < 16; ++u) {
-                    v += part[u];
-                    if (blk0 + u < bx) vb += part[u];
-                    if (blk0 + u == bx) own_r[it] = part[u];
-                }
-            }
-            tot[i] = v;
-            bef[i] = vb;
-        }
-    }
-    __syncthreads();
-    // threshold: the largest score s with C(s) >= k (C(0) = number of scored tokens >= k)
-    if (k > 0) {
-        for (int i = tid; i < G * kBinsW; i += kThreads) {
-            const int j = i / kBinsW, s = i - j * kBinsW;
-            if (tot[j * kRow + s] >= k) atomicMax(&thr[j], s);
-        }
-    }
-    __syncthreads();
-    if (k > 0) {
-#pragma unroll
-        for (int it = 0; it < kIter; ++it) {
-            const int i = tid + it * kThreads;
-            if (i < G * kRow) {
-                const int j = i / kRow, col = i - j * kRow;
-                if (col == thr[j]) own_ge_s[j] = own_r[it];
-                if (col == thr[j] + 1) own_gt_s[j] = own_r[it];
-            }
-        }
-    }
-    __syncthreads();
-    if (tid < G) {
-        const int j = tid;
-        const int64_t bh = bh0 + j;
-        const int T = k > 0 ? thr[j] : kBinsW;                           // k = 0: nothing reaches the threshold
-        int r = 0, gt = 0, ge = 0, own_eq = 0;
-        if (k > 0) {
-            r = k - tot[j * kRow + T + 1];                               // slot b + 1 holds 0
-            ge = bef[j * kRow + T];                                      // #{score >= T} before this block
-            gt = bef[j * kRow + T + 1];
-            own_eq = own_ge_s[j] - own_gt_s[j];                          // #{score == T} inside this block
-        }
-        const int eq_before = ge - gt, left = r - eq_before;
-        const int bs = (int)min((int64_t)n, (int64_t)bx * block_tokens);   // always-kept tokens before this block
-        thr[j] = T;
-        posb[j] = gt + min(eq_before, r) + min(lo, bs) + max(0, bs - hi);
-        quotab[j] = left >= own_eq ? kAllTies : max(left, 0);
-        if (bx == 0) {
-            count[bh] = lo + k + (n - hi);
-            if (threshold) threshold[bh] = (uint8_t)(k > 0 ? min(T, 255) : 0);   // saturates for b >= 256
-        }
-    }
-    __syncthreads();
+    block_selection<G, W>(blk_cum, bh0, blocks_pitch, n_blocks, bx, block_tokens, n, lo, hi, k, tot, bef, thr, posb, quotab,
+                          own_ge_s, own_gt_s, count, threshold);
 
     // ---- pass 1: score the unit once; masks per 64-token step and head, counts per wave
     // A head whose ties all fit the quota at this block (or whose quota is used up) needs one mask only:
@@ -436,76 +451,9 @@ __global__ __launch_bounds__(kThreads) void topk_select_runs_kernel(KvView c, co
         }
     }
 
-    if (tid < G) { thr[tid] = -1; own_ge_s[tid] = own_gt_s[tid] = 0; }
     if (tid < G * W) qs[tid] = q_codes[bh0 * W + tid];
-    // cumulative counts from the per-block rows in one trip to memory (see topk_select_wide_kernel)
-    constexpr int kIter = (G * kRow + kThreads - 1) / kThreads;
-    int own_r[kIter];
-#pragma unroll
-    for (int it = 0; it < kIter; ++it) {
-        const int i = tid + it * kThreads;
-        own_r[it] = 0;
-        if (i < G * kRow) {
-            const int j = i / kRow, col = i - j * kRow;
-            const int32_t* p = blk_cum + (bh0 + j) * blocks_pitch * kRow + col;
-            int v = 0, vb = 0;
-            for (int blk0 = 0; blk0 < n_blocks; blk0 += 16) {
-                int part[16];
-#pragma unroll
-                for (int u = 0; u < 16; ++u) part[u] = blk0 + u < n_blocks ? p[(int64_t)(blk0 + u) * kRow] : 0;
-#pragma unroll
-                for (int u = 0; u < 16; ++u) {
-                    v += part[u];
-                    if (blk0 + u < bx) vb += part[u];
-                    if (blk0 + u == bx) own_r[it] = part[u];
-                }
-            }
-            tot[i] = v;
-            bef[i] = vb;
-        }
-    }
-    __syncthreads();
-    if (k > 0) {
-        for (int i = tid; i < G * kBinsW; i += kThreads) {
-            const int j = i / kBinsW, sc = i - j * kBinsW;
-            if (tot[j * kRow + sc] >= k) atomicMax(&thr[j], sc);
-        }
-    }
-    __syncthreads();
-    if (k > 0) {
-#pragma unroll
-        for (int it = 0; it < kIter; ++it) {
-            const int i = tid + it * kThreads;
-            if (i < G * kRow) {
-                const int j = i / kRow, col = i - j * kRow;
-                if (col == thr[j]) own_ge_s[j] = own_r[it];
-                if (col == thr[j] + 1) own_gt_s[j] = own_r[it];
-            }
-        }
-    }
-    __syncthreads();
-    if (tid < G) {
-        const int j = tid;
-        const int64_t bh = bh0 + j;
-        const int T = k > 0 ? thr[j] : kBinsW;
-        int r = 0, gt = 0, ge = 0, own_eq = 0;
-        if (k > 0) {
-            r = k - tot[j * kRow + T + 1];
-            ge = bef[j * kRow + T];
-            gt = bef[j * kRow + T + 1];
-            own_eq = own_ge_s[j] - own_gt_s[j];
-        }
-        const int eq_before = ge - gt, left = r - eq_before;
-        const int bs = (int)min((int64_t)n, (int64_t)bx * block_tokens);
-        thr[j] = T;
-        posb[j] = gt + min(eq_before, r) + min(lo, bs) + max(0, bs - hi);
-        quotab[j] = left >= own_eq ? kAllTies : max(left, 0);
-        if (bx == 0) {
-            count[bh] = lo + k + (n - hi);
-            if (threshold) threshold[bh] = (uint8_t)(k > 0 ? min(T, 255) : 0);
-        }
-    }
-    __syncthreads();
+    block_selection<G, W>(blk_cum, bh0, blocks_pitch, n_blocks, bx, block_tokens, n, lo, hi, k, tot, bef, thr, posb, quotab,
+                          own_ge_s, own_gt_s, count, threshold);
 
     // ---- lane runs and masks
     unsigned sel[G], tie[G];
