@@ -100,6 +100,19 @@ def assert_codes_match(gpu_codes: np.ndarray, ref_codes: np.ndarray, act: np.nda
     return int(bits.sum())
 
 
+def round_to_bf16(x: np.ndarray) -> np.ndarray:
+    """fp64 values rounded to the nearest bf16 (ties to even), returned as fp64."""
+    return W.bf16_bits_to_f32(W.f32_to_bf16_bits(np.asarray(x, dtype=np.float32))).astype(np.float64)
+
+
+# The output is bf16, so half a bf16 unit of rounding (up to 2^-9 |ref|, 1.95e-3 at 1.0) sits in every
+# comparison with the fp64 oracle.  Against the oracle's value rounded to bf16 only the kernel's own
+# error is left: an fp32 result within rounding of the true value rounds to the same bf16 number or,
+# when the true value lies next to a rounding boundary, to its neighbour (one unit, at most 2^-7 |ref|);
+# OWN_FLOOR covers outputs near zero, where fp32 accumulation error exceeds the tiny bf16 unit.
+OWN_RTOL, OWN_FLOOR = 2.0 ** -7, 5e-5
+
+
 def assert_out_close(gpu_out_bf16: torch.Tensor, ref: np.ndarray, what: str):
     got = bf16_host_f64(gpu_out_bf16)
     err = np.abs(got - ref)
@@ -107,3 +120,11 @@ def assert_out_close(gpu_out_bf16: torch.Tensor, ref: np.ndarray, what: str):
     assert np.all(np.isfinite(got)), f"{what}: non-finite output"
     worst = float((err - tol).max())
     assert worst <= 0, f"{what}: max |err| {float(err.max()):.3e} exceeds {ATOL} + {RTOL}|ref| by {worst:.3e}"
+    ref16 = round_to_bf16(ref)
+    own = np.abs(got - ref16)
+    own_tol = OWN_RTOL * np.abs(ref16) + OWN_FLOOR
+    worst_own = float((own - own_tol).max())
+    assert worst_own <= 0, (f"{what}: kernel's own error (against the oracle rounded to bf16) {float(own.max()):.3e} "
+                            f"exceeds one bf16 unit + {OWN_FLOOR} by {worst_own:.3e}")
+    return {"max_abs_err": float(err.max()), "max_own_err": float(own.max()),
+            "same_bf16_frac": float((own == 0).mean())}

@@ -4,7 +4,9 @@ configuration bench.py times, on sampled (sequence, KV head) pairs.
 Inputs are drawn on the device (seeded); for every sampled pair the K/V rows of that head are copied
 to the host and the oracle runs the whole step on them as a one-head contiguous cache (also for the
 paged configuration, which thereby checks the page-table addressing).  Stages as in the small tests:
-codes bit-exact outside |activation| <= 1e-3, then TOPK and GATHER-ATT on the oracle's codes.
+codes bit-exact outside |activation| <= 1e-3, then TOPK and GATHER-ATT on the oracle's codes.  The dense
+baseline kernel (hashattn_dense_attend) runs on the same cache and is compared with the oracle's dense
+SDPA for the same sampled pairs.
 """
 import math
 
@@ -112,6 +114,8 @@ def run_sampled(cfg, seed, pairs, extra_rows=0):
         flips += assert_codes_match(gpu_q_codes[b, kvh * g:(kvh + 1) * g], res["q_codes"][0], act_q[0], "query codes")
         hv.put_codes(codes[0, 0, :n1])
         qc_dev[b, kvh * g:(kvh + 1) * g] = torch.from_numpy(res["q_codes"][0].view(np.int32)).to(DEV)
+        # dense SDPA over all n1 tokens of this head (section 3.1): what hashattn_dense_attend must give
+        res["dense"] = np.stack([oracle.dense_attend(ocache, 0, 0, q_host[0, j], n1, scale) for j in range(g)])
         refs[(b, kvh)] = res
 
     idx = torch.full_like(s.idx, -7)
@@ -120,6 +124,8 @@ def run_sampled(cfg, seed, pairs, extra_rows=0):
     out = torch.zeros_like(s.out)
     ctx.hashattn_score_topk(qc_dev, s.cache, s.B, s.k_per_seq, s.k_max, idx, count, thr)
     ctx.hashattn_gather_attend(s.q, s.cache, idx, count, s.B, s.k_max, s.scale, out)
+    dense = torch.full_like(s.out, float("nan"))
+    ctx.hashattn_dense_attend(s.q, s.cache, s.B, s.scale, dense)        # the split shape bench.py times
     torch.cuda.synchronize()
     idx_h, count_h, thr_h = idx.cpu().numpy(), count.cpu().numpy(), thr.cpu().numpy()
     for (b, kvh), res in refs.items():
@@ -131,6 +137,8 @@ def run_sampled(cfg, seed, pairs, extra_rows=0):
             assert np.all(idx_h[b, h, cnt:] == -7)
             assert thr_h[b, h] == res["threshold"][0, j]
         assert_out_close(out[b, kvh * g:(kvh + 1) * g], res["out"][0], f"gather_attend (b={b}, kvh={kvh})")
+        assert_out_close(dense[b, kvh * g:(kvh + 1) * g], res["dense"], f"dense_attend (b={b}, kvh={kvh})")
+    assert torch.isfinite(dense.float()).all()
     return flips
 
 
