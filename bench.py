@@ -1,21 +1,26 @@
 #!/usr/bin/env python3
 """Benchmark of the HashAttention decode layer-step on one MI355X.
 
-A step is one pass of the whole hot path over one layer: encode query -> SCORE + TOPK ->
-GATHER-ATT (preceded by the one-token append where the workload has one).  Steps walk a ring of
-distinct layers (own K/V, codes and mapping weights) whose codes and weights alone exceed the 256 MB
-Infinity Cache, so a step reads everything from HBM, as a decode that streams the model's weights
-between two visits of a layer does.  A whole sweep over the ring is
-captured in one HIP graph and replayed, which removes the host's launch cost from the step as a
-serving loop would.
+A step is one pass of the whole hot path over one layer: [one-token append ->] encode query ->
+SCORE + TOPK -> GATHER-ATT.  Steps walk a ring of distinct layers (own K/V, codes and mapping
+weights) whose codes and weights alone exceed the 256 MB Infinity Cache, so a step reads everything
+from HBM, as a decode that streams the model's weights between two visits of a layer does.  A whole
+sweep over the ring is captured in one HIP graph and replayed, which removes the host's launch cost
+from the step as a serving loop would.
 
-Prints ONE JSON line: whole-step effective GB/s (algorithmic bytes = key codes + gathered K/V rows
-+ Q/O), the roofline record of the dominant kernel (GATHER-ATT) from HIP-event timing, the speed-up
-over the in-house dense decode kernel on the same buffers, and the CPU oracle timed on the host.
+The headline workload is the largest single-GPU configuration (C2: 16 sequences of 131072 tokens,
+k = 4096, with the one-token append).  Prints ONE JSON line for it: whole-step effective GB/s
+(algorithmic bytes = key codes + gathered K/V rows + Q/O), the roofline record of the dominant kernel
+(GATHER-ATT), the speed-up over the in-house dense decode kernel on the same buffers, the CPU oracle
+timed on a stated sample of the same layer, a parity check of that sample, and (key "other_workloads")
+the step times of the other configurations measured in the same process.
 """
 from __future__ import annotations
 
 import argparse
+import gc
+import glob
+import hashlib
 import json
 import math
 import os
@@ -29,27 +34,7 @@ sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
 METRIC = "µs/layer decode step + effective HBM GB/s (% of peak), 32× sparsity, 1 GPU"
-
-
-def parse_args():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=640)
-    ap.add_argument("--warmup", type=int, default=64)
-    ap.add_argument("--workload", default="C1", choices=list(WORKLOADS),
-                    help="C1 = Llama-3.1-8B layer, B=1, N=32768, k=1024 (the headline configuration)")
-    ap.add_argument("--ring", type=int, default=0, help="distinct layers walked by the steps (0 = per workload)")
-    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-dense", action="store_true")
-    ap.add_argument("--score-table", action="store_true",
-                    help="also time SCORE + TOPK alone on uniform random codes of 32..512 bits at this workload's shape")
-    ap.add_argument("--sink", type=int, default=0, help="always keep this many first tokens (k counts the rest)")
-    ap.add_argument("--local", type=int, default=0, help="always keep this many most recent tokens")
-    ap.add_argument("--calibration-copy", action="store_true",
-                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
-    return ap.parse_args()
-
+DEV = "cuda:0"
 
 # workload name -> (config factory, ring length): the steps walk a ring of distinct layers whose key codes and mapping weights
 # alone exceed the 256 MB Infinity Cache (the K/V rows are loaded with the non-temporal hint and do not
@@ -64,6 +49,32 @@ WORKLOADS = {
     "C3-16x": (lambda W: W.scaled(W.c3(k=32768), name="C3-16x"), 20),
     "C4": (lambda W: W.c4(), 7),
 }
+HEADLINE = "C2"
+OTHERS_DEFAULT = "C1,C1-128K,C3,C4"
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=640)
+    ap.add_argument("--warmup", type=int, default=64)
+    ap.add_argument("--workload", default=HEADLINE, choices=list(WORKLOADS),
+                    help="C2 = Llama-3.1-8B layer, B=16, N=131072, k=4096, one-token append (the headline: the "
+                         "largest single-GPU configuration)")
+    ap.add_argument("--also", default=None,
+                    help="comma-separated workloads whose step time is added under 'other_workloads' "
+                         f"(default '{OTHERS_DEFAULT}' when the headline workload runs, none otherwise; '' = none)")
+    ap.add_argument("--ring", type=int, default=0, help="distinct layers walked by the steps (0 = per workload)")
+    ap.add_argument("--no-graph", action="store_true", help="launch eagerly instead of replaying a HIP graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--score-table", action="store_true",
+                    help="also time SCORE + TOPK alone on uniform random codes of 32..512 bits at this workload's shape")
+    ap.add_argument("--sink", type=int, default=0, help="always keep this many first tokens (k counts the rest)")
+    ap.add_argument("--local", type=int, default=0, help="always keep this many most recent tokens")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
+    return ap.parse_args()
 
 
 def workload_config(name):
@@ -72,18 +83,8 @@ def workload_config(name):
     return make(W), ring
 
 
-def device_layer_from_host(L, torch, ha):
-    """Layer 0 of the ring: the numpy arrays of workloads.make_layer, so the oracle sees the same bytes."""
-    from paper_2412_14468_amd.runner import LayerState
-    dev = "cuda:0"
-    as_bf16 = lambda a: torch.from_numpy(a.view(np.int16)).to(dev).view(torch.bfloat16)
-    return LayerState(as_bf16(L.q), as_bf16(L.k), as_bf16(L.v), torch.from_numpy(L.seq_lens.copy()).to(dev),
-                      int(L.seq_lens.max()), [torch.from_numpy(w).to(dev) for w in L.w_q],
-                      [torch.from_numpy(w).to(dev) for w in L.w_kv], None, int(L.k_per_seq.max()))
-
-
-def device_layer_synthetic(cfg, seed, torch):
-    """Ring layers drawn on the device by the same recipe (workloads.device_tensors)."""
+def device_layer_synthetic(cfg, seed):
+    """One ring layer drawn on the device by the recipe of workloads.device_tensors."""
     import workloads as W
     from paper_2412_14468_amd.runner import layer_from_tensors
     t = W.device_tensors(cfg, seed)
@@ -96,15 +97,31 @@ def describe_lengths(v):
     return str(v[0]) if min(v) == max(v) else f"{min(v)}..{max(v)} (sum {sum(v)})"
 
 
-def stored_traffic(workload):
-    """HBM bytes per GATHER-ATT launch from the committed rocprofv3 --pmc summary, if there is one
-    (counters cannot be read from inside this process)."""
-    path = os.path.join(ROOT, "profiles", "gather_attend_traffic.json")
+def source_id():
+    """Identity of the kernel sources a profile was taken with (first 16 hex digits of their SHA-256)."""
+    h = hashlib.sha256()
+    files = sorted(glob.glob(os.path.join(ROOT, "paper_2412_14468_amd", "csrc", "*")))
+    for path in files + [os.path.join(ROOT, "include", "hashattn.h")]:
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+def stored_profile(workload):
+    """What the committed rocprofv3 summaries hold for this workload (profiles/kernel_profiles.json):
+    average duration of the dominant kernel alone and HBM bytes per launch from the --pmc runs.  Counters
+    cannot be read from inside this process, so these are stored figures; `current` says whether the
+    kernel sources are still the ones they were measured with."""
+    path = os.path.join(ROOT, "profiles", "kernel_profiles.json")
     try:
         with open(path) as f:
-            return json.load(f).get(workload)
+            rec = json.load(f).get(workload)
     except (OSError, ValueError):
         return None
+    if rec:
+        rec = dict(rec)
+        rec["current"] = rec.get("source_id") == source_id()
+    return rec
 
 
 def time_region(torch, fn, reps):
@@ -143,35 +160,162 @@ def event_time_us(torch, fn, reps):
     return e0.elapsed_time(e1) * 1e3 / reps
 
 
-def main():
-    args = parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on one GPU only (the decode hot path of one attention layer); "
-              "use --gpus 1", file=sys.stderr)
-        sys.exit(2)
+# ------------------------------------------------------------------ host copies of sampled sequences
+def bits_of(torch, t):
+    """bf16 / int32 device tensor -> numpy bit patterns."""
+    if t.dtype == torch.bfloat16:
+        return t.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.contiguous().cpu().numpy().view(np.uint32)
+
+
+def sequence_rows(torch, s, tensor, b, n, page_size):
+    """Rows of the first n tokens of sequence b, all KV heads, in token order: [H_kv][n][...]."""
+    if s.page_table is None:
+        return tensor[b, :, :n]
+    t = torch.arange(n, device=DEV)
+    return tensor[s.page_table[b, t // page_size].long(), :, t % page_size].transpose(0, 1)
+
+
+def put_sequence_codes(torch, s, b, codes_host, page_size):
+    """codes_host [H_kv][n] uint32 -> the code store of sequence b."""
+    n = codes_host.shape[1]
+    src = torch.from_numpy(np.ascontiguousarray(codes_host).view(np.int32)).to(DEV)
+    if s.page_table is None:
+        s.codes[b, :, :n] = src
+    else:
+        t = torch.arange(n, device=DEV)
+        s.codes[s.page_table[b, t // page_size].long(), :, t % page_size] = src.transpose(0, 1)
+
+
+def oracle_leg(torch, ha, runner, W, ctx, cfg, s0, args, alg_bytes_all, budget_s=12.0):
+    """CPU oracle on a bounded sample of ring layer 0 (its first sequences, every head), timed on the
+    host cores, and the parity of the HIP path with it on that sample.
+
+    The sampled sequences' K/V rows, queries and mapping weights are copied back from the device
+    tensors the timed steps ran on; the oracle builds its own key codes from them (untimed: prefill
+    side) and runs whole layer-steps.  Parity is staged as in tests/: the GPU's own codes are
+    compared bit by bit (they may differ where the pre-sign activation is within rounding of 0), then
+    SCORE + TOPK + GATHER-ATT run on the oracle's codes, where index sets must be identical."""
+    import oracle
+    B, Hq, Hkv, d, ps = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.page_size
+    nb = min(B, 2)
+    seqs = list(range(nb))
+    lens0 = np.array([int(s0.lens_host[b]) for b in seqs], dtype=np.int32)
+    step_new = 1 if cfg.append else 0
+    cap = int(lens0.max()) + step_new
+    cap += (-cap) % 4
+    k_host = np.zeros((nb, Hkv, cap, d), dtype=np.uint16)
+    v_host = np.zeros_like(k_host)
+    for i, b in enumerate(seqs):
+        n0 = int(lens0[i])
+        k_host[i, :, :n0] = bits_of(torch, sequence_rows(torch, s0, s0.k, b, n0, ps))
+        v_host[i, :, :n0] = bits_of(torch, sequence_rows(torch, s0, s0.v, b, n0, ps))
+    codes = np.zeros((nb, Hkv, cap), dtype=np.uint32)
+    olens = lens0.copy()
+    ocache = oracle.Cache(k_host, v_host, codes, olens)
+    phi_q = oracle.Mlp([w.cpu().numpy() for w in s0.phi_q.weights])
+    phi_kv = oracle.Mlp([w.cpu().numpy() for w in s0.phi_kv.weights])
+    q_host = bits_of(torch, s0.q[:nb])
+    kps = np.array([int(s0.k_host[b]) for b in seqs], dtype=np.int32)
+    kw = {}
+    if cfg.append:
+        kw = dict(k_new=bits_of(torch, s0.k_new[:nb, :, 0]), v_new=bits_of(torch, s0.v_new[:nb, :, 0]))
+    t0 = time.perf_counter()
+    oracle.encode_keys(phi_kv, ocache, None, None, max(int(lens0.max()), 1))          # prefill side, not timed
+    prefill_s = time.perf_counter() - t0
+    scale = 1.0 / math.sqrt(d)
+
+    def step():
+        olens[:] = lens0                     # an append step starts from the same cache state every time
+        return oracle.decode_step(phi_q, phi_kv, ocache, q_host, kps, scale, n_sink=args.sink, n_local=args.local, **kw)
+
+    times, res = [], None
+    t_all = time.perf_counter()
+    while len(times) < 3 or (time.perf_counter() - t_all < budget_s and len(times) < 40):
+        t0 = time.perf_counter()
+        res = step()
+        times.append(time.perf_counter() - t0)
+    cpu_s = float(np.median(times))
+    threads = oracle.num_threads()
+    cores = min(threads, nb * Hq)            # the step runs one (sequence, head) pair per thread
+    one_s = None
+    if cpu_s * min(threads, nb * Hq) < 6.0:  # the same step on one host thread, for reference, when it is short
+        oracle.set_threads(1)
+        t0 = time.perf_counter()
+        step()
+        one_s = time.perf_counter() - t0
+        oracle.set_threads(threads)
+    lens1 = [int(n) + step_new for n in lens0]
+
+    def attended(n, kk):
+        lo = min(args.sink, n)
+        hi = max(lo, n - args.local)
+        return lo + min(kk, hi - lo) + (n - hi)
+    sample_bytes = W.algorithmic_bytes(Hkv, Hq, d, lens1, [attended(n, int(kk)) for n, kk in zip(lens1, kps)])
+    whole_s = cpu_s * alg_bytes_all / sample_bytes
+    cpu = {"value": round(sample_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+           "sample": (f"sequence{'s' if nb > 1 else ''} {', '.join(map(str, seqs))} of {B} of ring layer 0, all {Hq} query heads "
+                      f"each ({nb * Hq} (sequence, head) pairs, {sample_bytes} algorithmic bytes), whole layer-step"
+                      f"{' incl. the append' if cfg.append else ''}, median of {len(times)} runs of {round(cpu_s * 1e3, 1)} ms; "
+                      f"rows copied back from the device tensors of the timed steps"),
+           "us_per_layer_step_sample": round(cpu_s * 1e6, 1),
+           "us_per_layer_step_scaled_to_workload": round(whole_s * 1e6, 1),
+           "one_thread_us_per_layer_step_sample": None if one_s is None else round(one_s * 1e6, 1),
+           "oracle_prefill_encode_s": round(prefill_s, 2)}
+
+    # ---- parity of the sample: GPU codes first, then the rest of the step on the oracle's codes
+    s0.seq_lens.copy_(s0.lens0_dev)
+    s0.cache.max_seq_len = s0.max_len0
+    runner.build_key_codes(ctx, s0)
+    if cfg.append:
+        ctx.hashattn_encode_keys(s0.phi_kv, s0.k_new, s0.v_new, s0.B, 1, s0.cache)
+    ctx.hashattn_encode_query(s0.phi_q, s0.q, s0.B, s0.q_codes)
+    torch.cuda.synchronize()
+    diff_bits = total_bits = 0
+    for i, b in enumerate(seqs):
+        n1 = lens1[i]
+        gpu_codes = bits_of(torch, sequence_rows(torch, s0, s0.codes, b, n1, ps))
+        x = gpu_codes ^ codes[i, :, :n1]
+        diff_bits += int(np.unpackbits(x[x != 0].view(np.uint8)).sum())
+        total_bits += int(x.size) * 32
+        put_sequence_codes(torch, s0, b, codes[i, :, :n1], ps)
+    q_same = bool(np.array_equal(bits_of(torch, s0.q_codes[:nb]), res["q_codes"]))
+    s0.q_codes[:nb] = torch.from_numpy(res["q_codes"].view(np.int32)).to(DEV)
+    runner.score_topk(ctx, s0)
+    runner.gather_attend(ctx, s0)
+    torch.cuda.synchronize()
+    got = s0.out[:nb].float().cpu().numpy().astype(np.float64)
+    cnt_gpu, idx_gpu = s0.count[:nb].cpu().numpy(), s0.idx[:nb].cpu().numpy()
+    same_sets = bool(np.array_equal(cnt_gpu, res["count"]))
+    if same_sets:
+        for i in range(nb):
+            for h in range(Hq):
+                c = int(res["count"][i, h])
+                same_sets = same_sets and bool(np.array_equal(idx_gpu[i, h, :c], res["idx"][i, h, :c]))
+    err = np.abs(got - res["out"])
+    ref16 = W.bf16_bits_to_f32(W.f32_to_bf16_bits(res["out"].astype(np.float32))).astype(np.float64)
+    parity = {"sample": f"sequences {seqs} of ring layer 0, all heads", "key_code_bits_differing": diff_bits,
+              "key_code_bits_total": total_bits, "query_codes_equal": q_same,
+              "index_sets_equal_on_oracle_codes": same_sets,
+              "out_within_tol": bool(np.all(err <= 2e-3 + 1e-2 * np.abs(res["out"]))) if same_sets else None,
+              "max_abs_err": float(err.max()) if same_sets else None,
+              "max_abs_err_vs_oracle_rounded_to_bf16": float(np.abs(got - ref16).max()) if same_sets else None}
+    return cpu, parity
+
+
+# ------------------------------------------------------------------ one workload
+def run_workload(name, args, headline):
     import torch
     import paper_2412_14468_amd as ha
     from paper_2412_14468_amd import runner
     import workloads as W
 
-    assert torch.cuda.is_available(), "bench.py needs the MI355X"
-    torch.cuda.set_device(0)
-    ha.load()
-    cfg, ring_default = workload_config(args.workload)
-    ring = args.ring or ring_default
-    B, Hq, Hkv, d, N = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim, cfg.context
-    host_layer0 = args.workload == "C1" and not args.no_cpu_baseline      # numpy layer 0 feeds the oracle too
+    cfg, ring_default = workload_config(name)
+    ring = (args.ring if headline else 0) or ring_default
+    B, Hq, Hkv, d = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
 
     t_setup = time.perf_counter()
-    layers = []
-    L0 = None
-    if host_layer0:
-        L0 = W.make_layer(cfg)
-        s0 = device_layer_from_host(L0, torch, ha)
-        s0.lens_host, s0.k_host = L0.seq_lens.copy(), L0.k_per_seq.copy()
-        layers.append(s0)
-    while len(layers) < ring:
-        layers.append(device_layer_synthetic(cfg, W.BASE_SEED + 1000 * cfg.index + len(layers), torch))
+    layers = [device_layer_synthetic(cfg, W.BASE_SEED + 1000 * cfg.index + i) for i in range(ring)]
     n_cap = max(int(s.k.shape[2]) if s.page_table is None else int(s.page_table.shape[1]) * cfg.page_size for s in layers)
     k_max = max(s.k_max for s in layers)
     ctx = ha.Context(Hq, Hkv, B, n_cap, k_max + args.sink + args.local, page_size=cfg.page_size)
@@ -183,8 +327,8 @@ def main():
         s.max_len0 = s.cache.max_seq_len
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
-    if args.calibration_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda:0").random_(0, 255)
+    if headline and args.calibration_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=DEV).random_(0, 255)
         torch.empty_like(src).copy_(src)
         torch.cuda.synchronize()
         del src
@@ -229,20 +373,6 @@ def main():
         ks = [attended(n, kk) for n, kk in zip(lens_final, ks)]
     alg_bytes = W.algorithmic_bytes(Hkv, Hq, d, lens_final, ks)
     gbs = alg_bytes / (us_per_step * 1e-6) / 1e9
-    k = k_max
-
-    # ---- dominant kernel (GATHER-ATT) by HIP events on its own graph of `ring` launches
-    def gather_sweep():
-        for s in layers:
-            runner.gather_attend(ctx, s)
-    gather_bytes = W.gathered_bytes(Hq, d, lens_final, ks)
-    if args.no_graph:
-        gather_us = event_time_us(torch, gather_sweep, 10) / ring
-    else:
-        g_replay = capture(torch, gather_sweep)
-        g_replay()
-        gather_us = event_time_us(torch, g_replay, 10) / ring
-    gather_gbs = gather_bytes / (gather_us * 1e-6) / 1e9
 
     def stage_us(body):
         if args.no_graph:
@@ -251,6 +381,11 @@ def main():
         rp()
         return event_time_us(torch, rp, 10) / ring
 
+    # ---- the entry points one by one, by HIP events on their own graphs of `ring` launches
+    def gather_sweep():
+        for s in layers:
+            runner.gather_attend(ctx, s)
+
     def topk_sweep():
         for s in layers:
             runner.score_topk(ctx, s)
@@ -258,49 +393,11 @@ def main():
     def encq_sweep():
         for s in layers:
             ctx.hashattn_encode_query(s.phi_q, s.q, s.B, s.q_codes)
-    topk_us, encq_us = stage_us(topk_sweep), stage_us(encq_sweep)
+    gather_bytes = W.gathered_bytes(Hq, d, lens_final, ks)
+    code_bytes = 4 * Hkv * sum(lens_final)
+    gather_us, topk_us, encq_us = stage_us(gather_sweep), stage_us(topk_sweep), stage_us(encq_sweep)
+    gather_gbs = gather_bytes / (gather_us * 1e-6) / 1e9
 
-    # ---- prefill side: rebuilding the whole key-code store of one layer (not part of the decode step)
-    def rebuild():
-        runner.build_key_codes(ctx, layers[0])
-    rebuild()
-    enc_us = event_time_us(torch, rebuild, 3)
-    n_vec = sum(int(n) for n in layers[0].lens_host) * Hkv
-    dims = cfg.mlp_dims
-    mlp_flop = 2 * sum(a * b for a, b in zip(dims[:-1], dims[1:]))
-    key_encode = {"us": round(enc_us, 1), "Mvectors_per_s": round(n_vec / enc_us, 1),
-                  "algorithmic_TFLOPs": round(n_vec * mlp_flop / (enc_us * 1e-6) / 1e12, 1),
-                  "key_read_GBps": round(n_vec * d * 2 / (enc_us * 1e-6) / 1e9, 1),
-                  "note": "fp32-equivalent flops of the mapping; run as 2-3 bf16 MFMA passes per layer"}
-
-    # ---- SCORE + TOPK alone for signatures of 32..512 bits (the paper's SCORE latency table lists 64..512)
-    score_table = None
-    if args.score_table:
-        score_table = {}
-        gen = torch.Generator(device="cuda:0")
-        gen.manual_seed(W.BASE_SEED + 512)
-        s0 = layers[0]
-        for bits in (32, 64, 128, 256, 512):
-            words = bits // 32
-            wctx = ctx if bits == 32 else ha.Context(Hq, Hkv, B, n_cap, k_max, page_size=cfg.page_size, bits=bits)
-            n_ring = max(2, min(ring, (1 << 30) // max(1, s0.codes.numel() * 4 * words)))
-            shape = tuple(s0.codes.shape) + ((words,) if words > 1 else ())
-            rings = [(torch.randint(-2 ** 31, 2 ** 31 - 1, shape, dtype=torch.int32, device="cuda:0", generator=gen),
-                      torch.randint(-2 ** 31, 2 ** 31 - 1, (B, Hq) + ((words,) if words > 1 else ()), dtype=torch.int32,
-                                    device="cuda:0", generator=gen)) for _ in range(n_ring)]
-            caches = [ha.KvCache(s0.k, s0.v, cds, s0.seq_lens, s0.cache.max_seq_len, page_table=s0.page_table) for cds, _ in rings]
-
-            def wide_sweep():
-                for cache_w, (_, qcw) in zip(caches, rings):
-                    wctx.hashattn_score_topk(qcw, cache_w, B, s0.k_per_seq, s0.k_max, s0.idx, s0.count, s0.threshold)
-            rp = capture(torch, wide_sweep) if not args.no_graph else wide_sweep
-            rp()
-            us = event_time_us(torch, rp, 10) / n_ring
-            code_bytes = sum(int(n) for n in s0.lens_host) * Hkv * 4 * words
-            score_table[str(bits)] = {"us": round(us, 2), "code_GBps": round(code_bytes / (us * 1e-6) / 1e9, 1)}
-            del rings, caches
-
-    # ---- in-house dense decode on the same ring
     dense = None
     if not args.no_dense:
         def dense_sweep():
@@ -311,83 +408,147 @@ def main():
         dense = {"us_per_layer": round(dense_us, 3), "GBps": round(dense_bytes / (dense_us * 1e-6) / 1e9, 1),
                  "speedup_sparse_vs_dense": round(dense_us / us_per_step, 3)}
 
-    # ---- CPU oracle on the host cores, same arrays as ring layer 0
-    cpu = None
-    parity = None
-    if host_layer0:
-        import oracle
-        ok, ov = L0.k.copy(), L0.v.copy()
-        codes = np.zeros(ok.shape[:3], dtype=np.uint32)
-        ocache = oracle.Cache(ok, ov, codes, L0.seq_lens.copy())
-        phi_q, phi_kv = oracle.Mlp(L0.w_q), oracle.Mlp(L0.w_kv)
-        oracle.encode_keys(phi_kv, ocache, None, None, N)            # prefill-side, not timed
-        scale = 1.0 / math.sqrt(d)
-        times, res = [], None
-        t_all = time.perf_counter()
-        while len(times) < 3 or (time.perf_counter() - t_all < 10.0 and len(times) < 40):
-            t0 = time.perf_counter()
-            res = oracle.decode_step(phi_q, phi_kv, ocache, L0.q, L0.k_per_seq, scale, n_sink=args.sink, n_local=args.local)
-            times.append(time.perf_counter() - t0)
-        cpu_s = float(np.median(times))
-        cores = oracle.num_threads()
-        oracle.set_threads(1)                                        # the same step on one host thread, for reference
-        one = []
-        for _ in range(3):
-            t0 = time.perf_counter()
-            oracle.decode_step(phi_q, phi_kv, ocache, L0.q, L0.k_per_seq, scale, n_sink=args.sink, n_local=args.local)
-            one.append(time.perf_counter() - t0)
-        oracle.set_threads(cores)
-        cpu = {"value": round(alg_bytes / cpu_s / 1e9, 4), "unit": "GB/s", "us_per_layer_step": round(cpu_s * 1e6, 1),
-               "cores": cores, "kind": "oracle",
-               "sample": f"whole {cfg.name} layer-step (all {B * Hq} (sequence, head) pairs), median of {len(times)} runs",
-               "one_thread_us_per_layer_step": round(float(np.median(one)) * 1e6, 1)}
-        # parity of ring layer 0 against the oracle, staged as in tests/: the GPU's own codes are compared
-        # bit by bit (they may differ where the pre-sign activation is within rounding of 0), then SCORE +
-        # TOPK + GATHER-ATT run on the oracle's codes, where index sets must be identical
-        s0 = layers[0]
-        runner.build_key_codes(ctx, s0)
-        ctx.hashattn_encode_query(s0.phi_q, s0.q, s0.B, s0.q_codes)
-        torch.cuda.synchronize()
-        gpu_codes = s0.codes.cpu().numpy().view(np.uint32)
-        diff_bits = int(sum(bin(int(x)).count("1") for x in (gpu_codes ^ codes)[gpu_codes != codes]))
-        q_same = bool(np.array_equal(s0.q_codes.cpu().numpy().view(np.uint32), res["q_codes"]))
-        s0.codes.copy_(torch.from_numpy(codes.view(np.int32)).to("cuda:0"))
-        s0.q_codes.copy_(torch.from_numpy(res["q_codes"].view(np.int32)).to("cuda:0"))
-        runner.score_topk(ctx, s0)
-        runner.gather_attend(ctx, s0)
-        torch.cuda.synchronize()
-        got = s0.out.float().cpu().numpy().astype(np.float64)
-        n_att = int(res["count"].max())
-        same_sets = bool(np.array_equal(s0.count.cpu().numpy(), res["count"]) and
-                         np.array_equal(s0.idx.cpu().numpy()[:, :, :n_att], res["idx"][:, :, :n_att]))
-        err = np.abs(got - res["out"])
-        parity = {"key_code_bits_differing": diff_bits, "key_code_bits_total": int(codes.size) * 32,
-                  "query_codes_equal": q_same, "index_sets_equal_on_oracle_codes": same_sets,
-                  "out_within_tol": bool(np.all(err <= 2e-3 + 1e-2 * np.abs(res["out"]))) if same_sets else None,
-                  "max_abs_err": float(err.max()) if same_sets else None}
+    rec = {"name": cfg.name, "cfg": cfg, "ring": ring, "launch": launch, "us_per_step": us_per_step, "gbs": gbs,
+           "alg_bytes": alg_bytes, "lens_final": lens_final, "ks": ks, "k_max": k_max, "gather_us": gather_us,
+           "gather_bytes": gather_bytes, "gather_gbs": gather_gbs, "topk_us": topk_us, "encq_us": encq_us,
+           "code_bytes": code_bytes, "dense": dense, "setup_s": t_setup}
+    if not headline:
+        del layers, ctx
+        gc.collect()
+        torch.cuda.empty_cache()
+        return rec
 
+    # ---- prefill side: rebuilding the whole key-code store of one layer (not part of the decode step)
+    def rebuild():
+        runner.build_key_codes(ctx, layers[0])
+    rebuild()
+    enc_us = event_time_us(torch, rebuild, 3)
+    n_vec = sum(int(n) for n in layers[0].lens_host) * Hkv
+    dims = cfg.mlp_dims
+    mlp_flop = 2 * sum(a * b for a, b in zip(dims[:-1], dims[1:]))
+    rec["key_encode"] = {"us": round(enc_us, 1), "Mvectors_per_s": round(n_vec / enc_us, 1),
+                         "algorithmic_TFLOPs": round(n_vec * mlp_flop / (enc_us * 1e-6) / 1e12, 1),
+                         "key_read_GBps": round(n_vec * d * 2 / (enc_us * 1e-6) / 1e9, 1),
+                         "note": "fp32-equivalent flops of the mapping; run as 2-3 bf16 MFMA passes per layer"}
+
+    # ---- SCORE + TOPK alone for signatures of 32..512 bits (the paper's SCORE latency table lists 64..512)
+    rec["score_table"] = None
+    if args.score_table:
+        score_table = {}
+        gen = torch.Generator(device=DEV)
+        gen.manual_seed(W.BASE_SEED + 512)
+        s0 = layers[0]
+        for bits in (32, 64, 128, 256, 512):
+            words = bits // 32
+            wctx = ctx if bits == 32 else ha.Context(Hq, Hkv, B, n_cap, k_max, page_size=cfg.page_size, bits=bits)
+            n_ring = max(2, min(ring, (1 << 30) // max(1, s0.codes.numel() * 4 * words)))
+            shape = tuple(s0.codes.shape) + ((words,) if words > 1 else ())
+            rings = [(torch.randint(-2 ** 31, 2 ** 31 - 1, shape, dtype=torch.int32, device=DEV, generator=gen),
+                      torch.randint(-2 ** 31, 2 ** 31 - 1, (B, Hq) + ((words,) if words > 1 else ()), dtype=torch.int32,
+                                    device=DEV, generator=gen)) for _ in range(n_ring)]
+            caches = [ha.KvCache(s0.k, s0.v, cds, s0.seq_lens, s0.cache.max_seq_len, page_table=s0.page_table) for cds, _ in rings]
+
+            def wide_sweep():
+                for cache_w, (_, qcw) in zip(caches, rings):
+                    wctx.hashattn_score_topk(qcw, cache_w, B, s0.k_per_seq, s0.k_max, s0.idx, s0.count, s0.threshold)
+            rp = capture(torch, wide_sweep) if not args.no_graph else wide_sweep
+            rp()
+            us = event_time_us(torch, rp, 10) / n_ring
+            cb = sum(int(n) for n in s0.lens_host) * Hkv * 4 * words
+            score_table[str(bits)] = {"us": round(us, 2), "code_GBps": round(cb / (us * 1e-6) / 1e9, 1)}
+            del rings, caches
+        rec["score_table"] = score_table
+
+    # ---- CPU oracle on the host cores and parity, on a sample of ring layer 0
+    rec["cpu"] = rec["parity"] = None
+    if not args.no_cpu_baseline:
+        rec["cpu"], rec["parity"] = oracle_leg(torch, ha, runner, W, ctx, cfg, layers[0], args, alg_bytes)
+    del layers, ctx
+    gc.collect()
+    torch.cuda.empty_cache()
+    return rec
+
+
+def workload_text(r, args):
+    cfg = r["cfg"]
+    return (f"{cfg.name}: Llama-3.1-8B-shaped decode layer, B={cfg.batch}, N={describe_lengths(r['lens_final'])}, "
+            f"k={describe_lengths(r['ks'])} ({round(sum(r['lens_final']) / max(sum(r['ks']), 1))}x sparsity), "
+            f"{cfg.n_q_heads} q heads / {cfg.n_kv_heads} KV heads, d={cfg.head_dim}, "
+            f"mapping MLPs {'-'.join(map(str, cfg.mlp_dims))} fp32"
+            + (", paged KV (16 tokens/page)" if cfg.page_size else "")
+            + (", one-token append per step" if cfg.append else "")
+            + (f", first {args.sink} and last {args.local} tokens always kept (k counts them here)"
+               if args.sink or args.local else ""))
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the decode hot path of one attention layer); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    import paper_2412_14468_amd as ha
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    torch.cuda.set_device(0)
+    ha.load()
+    r = run_workload(args.workload, args, headline=True)
+    also = args.also if args.also is not None else (OTHERS_DEFAULT if args.workload == HEADLINE else "")
+    others = {}
+    for name in [w for w in also.split(",") if w]:
+        if name not in WORKLOADS or name == args.workload:
+            continue
+        o = run_workload(name, args, headline=False)
+        sg_us = o["topk_us"] + o["gather_us"]
+        others[name] = {"workload": workload_text(o, args), "us_per_layer_step": round(o["us_per_step"], 3),
+                        "GBps": round(o["gbs"], 1), "pct_of_hbm_peak": round(100.0 * o["gbs"] / HBM_PEAK_GBS, 2),
+                        "algorithmic_bytes_per_step": o["alg_bytes"], "ring_layers": o["ring"],
+                        "stages_us": {"encode_query": round(o["encq_us"], 3), "score_topk": round(o["topk_us"], 3),
+                                      "gather_attend": round(o["gather_us"], 3)},
+                        "score_plus_gather_pct_of_hbm_peak":
+                            round(100.0 * (o["code_bytes"] + o["gather_bytes"]) / (sg_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 2),
+                        "dense_baseline": o["dense"], "setup_s": round(o["setup_s"], 1)}
+
+    cfg = r["cfg"]
+    prof = stored_profile(args.workload)
+    frac_kernel = traffic = None
+    if prof:
+        if prof.get("gather_attend_kernel_avg_us"):
+            frac_kernel = round(r["gather_bytes"] / (prof["gather_attend_kernel_avg_us"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)
+        if prof.get("fetch_bytes") is not None:
+            traffic = {"fetch_bytes": prof["fetch_bytes"], "write_bytes": prof.get("write_bytes"),
+                       "total_bytes": prof["fetch_bytes"] + (prof.get("write_bytes") or 0),
+                       "measured_with_source_id": prof.get("source_id"), "current": prof["current"],
+                       "note": prof.get("traffic_note")}
+    sg_us = r["topk_us"] + r["gather_us"]
     line = {
-        "metric": METRIC, "value": round(gbs, 2), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": Wm,
-        "ms_per_step": round(us_per_step * 1e-3, 6), "us_per_layer_step": round(us_per_step, 3),
-        "pct_of_hbm_peak": round(100.0 * gbs / HBM_PEAK_GBS, 2), "higher_is_better": True, "scaling": "weak",
+        "metric": METRIC, "value": round(r["gbs"], 2), "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(r["us_per_step"] * 1e-3, 6), "us_per_layer_step": round(r["us_per_step"], 3),
+        "pct_of_hbm_peak": round(100.0 * r["gbs"] / HBM_PEAK_GBS, 2), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"{cfg.name}: Llama-3.1-8B-shaped decode layer, B={B}, N={describe_lengths(lens_final)}, "
-                               f"k={describe_lengths(ks)} ({round(sum(lens_final) / max(sum(ks), 1))}x sparsity), "
-                               f"{Hq} q heads / {Hkv} KV heads, d={d}, mapping MLPs {'-'.join(map(str, cfg.mlp_dims))} fp32"
-                               + (", paged KV (16 tokens/page)" if cfg.page_size else "")
-                               + (", one-token append per step" if cfg.append else "")
-                               + (f", first {args.sink} and last {args.local} tokens always kept (k counts them here)"
-                                  if args.sink or args.local else ""),
-                   "batch": B, "context": max(lens_final), "k": k, "ring_layers": ring, "launch": launch,
-                   "algorithmic_bytes_per_step": alg_bytes},
-        "roofline": {"bound": "hbm", "kernel": "hashattn_gather_attend = gather_attend_kernel + merge_partials_kernel",
-                     "achieved": round(gather_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                     "frac": round(gather_gbs / HBM_PEAK_GBS, 4), "traffic": stored_traffic(args.workload),
-                     "us_per_launch": round(gather_us, 3), "algorithmic_bytes_per_launch": gather_bytes},
-        "cpu_baseline": cpu,
-        "stages_us": {"encode_query": round(encq_us, 3), "score_topk": round(topk_us, 3),
-                      "gather_attend": round(gather_us, 3)},
-        "dense_baseline": dense, "key_encode_bulk": key_encode, "score_topk_by_bits": score_table, "parity_layer0": parity, "setup_s": round(t_setup, 1),
+        "config": {"workload": workload_text(r, args), "batch": cfg.batch, "context": max(r["lens_final"]), "k": r["k_max"],
+                   "ring_layers": r["ring"], "launch": r["launch"], "algorithmic_bytes_per_step": r["alg_bytes"]},
+        "roofline": {"bound": "hbm", "kernel": "gather_attend_kernel",
+                     "achieved": round(r["gather_gbs"], 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(r["gather_gbs"] / HBM_PEAK_GBS, 4),
+                     "frac_entry": round(r["gather_gbs"] / HBM_PEAK_GBS, 4), "frac_kernel": frac_kernel,
+                     "traffic": traffic, "us_per_launch": round(r["gather_us"], 3),
+                     "algorithmic_bytes_per_launch": r["gather_bytes"],
+                     "note": ("achieved, frac and frac_entry: algorithmic bytes of GATHER-ATT / HIP-event time of the entry point "
+                              "hashattn_gather_attend in this run (gather_attend_kernel followed by the small merge_partials_kernel); "
+                              "frac_kernel: the same bytes / the rocprofv3 average of gather_attend_kernel alone from "
+                              "profiles/kernel_profiles.json"
+                              + ("" if not prof else (", taken with these kernel sources" if prof["current"] else
+                                                      ", taken with OLDER kernel sources than this build")))},
+        "cpu_baseline": r["cpu"],
+        "stages_us": {"encode_query": round(r["encq_us"], 3), "score_topk": round(r["topk_us"], 3),
+                      "gather_attend": round(r["gather_us"], 3)},
+        "score_plus_gather_pct_of_hbm_peak":
+            round(100.0 * (r["code_bytes"] + r["gather_bytes"]) / (sg_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 2),
+        "dense_baseline": r["dense"], "key_encode_bulk": r["key_encode"], "score_topk_by_bits": r["score_table"],
+        "parity_sample": r["parity"], "other_workloads": others or None, "kernel_source_id": source_id(),
+        "setup_s": round(r["setup_s"], 1),
     }
     print(json.dumps(line, ensure_ascii=False))
 
