@@ -73,8 +73,9 @@ typedef struct {
 
 /* Mapping network F of phi (section 4.1, eq. 2): n_layers weight matrices with
  * SiLU between them and no activation before the sign.  Layer l maps dims[l]
- * inputs to dims[l+1] outputs as y = x W (+ bias).  dims[0] = 128, hidden
- * widths <= 256 and multiples of 32, dims[n_layers] = 32.  One network per head. */
+ * inputs to dims[l+1] outputs as y = x W (+ bias).  dims[0] = 128; a hidden
+ * width is 32, 64, 128 or 256; dims[n_layers] = the context's `bits`.  One
+ * network per head.  Other shapes are refused with HASHATTN_UNSUPPORTED. */
 typedef struct {
     int32_t n_heads;
     int32_t n_layers;         /* 1, 2 or 3 */
@@ -95,7 +96,11 @@ typedef struct {
     int64_t n_pages;          /* paged: number of physical pages P; contiguous: ignored */
     int32_t max_pages_per_seq;/* paged only */
     int32_t max_seq_len;      /* HOST upper bound on seq_lens[*] valid for this call (sizes the grids);
-                                 hashattn_encode_keys in append mode adds n_new to it */
+                                 hashattn_encode_keys in append mode adds n_new to it.  Calls recorded
+                                 into a HIP graph keep the bound they were captured with: the device
+                                 lengths advance on every replay, this host field does not, so a caller
+                                 that replays appends captures with a bound that covers all replays
+                                 and keeps the field up to date itself */
 } hashattn_kv;
 
 /* Create / destroy a context on the current HIP device.  Allocates scratch
@@ -105,9 +110,15 @@ hashattn_status hashattn_destroy(hashattn_ctx* ctx);
 const char* hashattn_last_error(const hashattn_ctx* ctx);
 /* Bytes of device scratch the context holds. */
 int64_t hashattn_scratch_bytes(const hashattn_ctx* ctx);
+/* For tests of the consistency check described at hashattn_encode_keys: leaves
+ * the append kernel's block counter, on `stream`, as a launch that stopped
+ * after `value` of its blocks would (>= 0; 0 is the normal state).  Not needed
+ * by any caller of the path. */
+hashattn_status hashattn_selftest_set_append_counter(hashattn_ctx* ctx, int32_t value, void* stream);
 
-/* Key signatures phi_int,kv(k), "computed and cached along with KV Cache"
- * (section 4.1, Implementation; phi_kv reads the key vector only).
+/* Key signatures phi_int,kv(k), computed when a token enters the KV cache and
+ * stored beside it (section 4.1, "Implementation" paragraph; phi_kv reads the
+ * key vector only).
  *   append mode (k_new, v_new != NULL): k_new, v_new are dev bf16
  *     [batch][H_kv][n_new][128].  For every sequence b the n_new rows are
  *     written at positions seq_lens[b] .. seq_lens[b]+n_new-1 of the cache
@@ -118,7 +129,12 @@ int64_t hashattn_scratch_bytes(const hashattn_ctx* ctx);
  *   in-place mode (k_new == NULL, v_new == NULL): the rows are already in the
  *     cache; the codes of the last min(n_new, seq_lens[b]) tokens of every
  *     sequence are recomputed from the cached keys.  seq_lens is unchanged.
- *     n_new = max_seq_len rebuilds the whole store (prefill). */
+ *     n_new = max_seq_len rebuilds the whole store (prefill).
+ * The decode-time append (few rows) moves the lengths from inside its one
+ * kernel, through a block counter in the context's scratch that every launch
+ * must find complete.  A launch that finds it otherwise (an earlier append
+ * on this context did not run to its end) reports it: from then on every call
+ * on the context returns HASHATTN_HIP_ERROR and hashattn_last_error() says why. */
 hashattn_status hashattn_encode_keys(hashattn_ctx* ctx, const hashattn_mlp* phi_kv,
                                      const void* k_new, const void* v_new,
                                      int32_t batch, int64_t n_new,

@@ -66,6 +66,8 @@ def load() -> C.CDLL:
     L.hashattn_last_error.argtypes = [vp]
     L.hashattn_scratch_bytes.restype = i64
     L.hashattn_scratch_bytes.argtypes = [vp]
+    L.hashattn_selftest_set_append_counter.restype = i32
+    L.hashattn_selftest_set_append_counter.argtypes = [vp, i32, vp]
     L.hashattn_encode_keys.restype = i32
     L.hashattn_encode_keys.argtypes = [vp, C.POINTER(MlpStruct), vp, vp, i32, i64, C.POINTER(KvStruct), vp]
     L.hashattn_encode_query.restype = i32
@@ -177,6 +179,9 @@ class Context:
     @property
     def scratch_bytes(self) -> int:
         return int(load().hashattn_scratch_bytes(self.h))
+
+    def hashattn_selftest_set_append_counter(self, value: int, stream=None) -> None:
+        self._check(load().hashattn_selftest_set_append_counter(self.h, int(value), _stream(stream)))
 
     # --- the four calls of the path (+ the dense comparison kernel) ---
     def hashattn_encode_keys(self, phi_kv: Mlp, k_new, v_new, batch: int, n_new: int, cache: KvCache,

@@ -3,6 +3,7 @@
 #include "../../include/hashattn.h"
 #include "kernels.hpp"
 
+#include <climits>
 #include <cstdarg>
 #include <cstdio>
 #include <cstdlib>
@@ -17,7 +18,9 @@ struct hashattn_ctx {
     int32_t* blk_cum;
     int32_t blocks_pitch;
     uint4* frags;                 // bf16 weight fragments of the matrix-core key encoder, per KV head
-    int32_t* append_done;         // block counter of the decode-time append kernel (zero between calls)
+    uint32_t* append_done;        // two-word block counter of the decode-time append kernel (see finish_append)
+    int32_t* append_fault_host;   // pinned host word an append launch raises when it finds that counter inconsistent
+    int32_t* append_fault_dev;    // the device's address of the same word
     int64_t frag_bytes;
     // split partials shared by GATHER-ATT and the dense kernel
     float* part;
@@ -32,7 +35,7 @@ constexpr int kMinUnit = 256;          // tokens per wave unit: one 16-byte load
 constexpr int kMaxUnit = 2048;
 constexpr int kMaxSplits = 256;
 
-char g_create_err[256] = "";
+thread_local char g_create_err[256] = "";     // last failure of a call without a context, per host thread
 
 hashattn_status fail(hashattn_ctx* ctx, hashattn_status st, const char* fmt, ...)
 {
@@ -78,22 +81,24 @@ ha::MlpView view_of(const hashattn_mlp* m)
     return v;
 }
 
-hashattn_status check_cache(hashattn_ctx* ctx, const hashattn_kv* kv, int batch, bool need_codes, const char* what)
+// ctx may be NULL (the entry point without a context): the message then goes to the thread's buffer.
+hashattn_status check_cache(hashattn_ctx* ctx, const hashattn_config& cfg, const hashattn_kv* kv, int batch, bool need_codes,
+                            const char* what)
 {
     if (!kv) return fail(ctx, HASHATTN_INVALID_ARG, "%s: cache is NULL", what);
     if (batch < 1) return fail(ctx, HASHATTN_INVALID_ARG, "%s: batch %d < 1", what, batch);
-    if (batch > ctx->cfg.max_batch)
-        return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "%s: batch %d exceeds max_batch %d", what, batch, ctx->cfg.max_batch);
+    if (batch > cfg.max_batch)
+        return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "%s: batch %d exceeds max_batch %d", what, batch, cfg.max_batch);
     if (!kv->k || !kv->v || !kv->seq_lens) return fail(ctx, HASHATTN_INVALID_ARG, "%s: k, v or seq_lens is NULL", what);
     if (need_codes && !kv->codes) return fail(ctx, HASHATTN_INVALID_ARG, "%s: codes is NULL", what);
     if (!aligned(kv->k, 16) || !aligned(kv->v, 16)) return fail(ctx, HASHATTN_INVALID_ARG, "%s: k/v not 16-byte aligned", what);
     if (kv->codes && !aligned(kv->codes, 16)) return fail(ctx, HASHATTN_INVALID_ARG, "%s: codes not 16-byte aligned", what);
     if (!aligned(kv->seq_lens, 4)) return fail(ctx, HASHATTN_INVALID_ARG, "%s: seq_lens not 4-byte aligned", what);
     if (kv->max_seq_len < 0) return fail(ctx, HASHATTN_INVALID_ARG, "%s: max_seq_len %d < 0", what, kv->max_seq_len);
-    if (kv->max_seq_len > ctx->cfg.max_context)
+    if (kv->max_seq_len > cfg.max_context)
         return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "%s: max_seq_len %d exceeds max_context %lld", what,
-                    kv->max_seq_len, (long long)ctx->cfg.max_context);
-    if (ctx->cfg.page_size == 0) {
+                    kv->max_seq_len, (long long)cfg.max_context);
+    if (cfg.page_size == 0) {
         if (kv->page_table) return fail(ctx, HASHATTN_INVALID_ARG, "%s: page_table given to a contiguous context", what);
         if (kv->n_max < 1 || (kv->n_max & 3)) return fail(ctx, HASHATTN_INVALID_ARG, "%s: n_max %lld must be a positive multiple of 4", what, (long long)kv->n_max);
         if (kv->max_seq_len > kv->n_max) return fail(ctx, HASHATTN_INVALID_ARG, "%s: max_seq_len %d exceeds n_max %lld", what, kv->max_seq_len, (long long)kv->n_max);
@@ -107,7 +112,12 @@ hashattn_status check_cache(hashattn_ctx* ctx, const hashattn_kv* kv, int batch,
     return HASHATTN_OK;
 }
 
-ha::KvView view_of(const hashattn_ctx* ctx, const hashattn_kv* kv)
+hashattn_status check_cache(hashattn_ctx* ctx, const hashattn_kv* kv, int batch, bool need_codes, const char* what)
+{
+    return check_cache(ctx, ctx->cfg, kv, batch, need_codes, what);
+}
+
+ha::KvView view_of(int n_kv_heads, const hashattn_kv* kv)
 {
     ha::KvView v{};
     v.k = static_cast<const uint16_t*>(kv->k);
@@ -117,9 +127,11 @@ ha::KvView view_of(const hashattn_ctx* ctx, const hashattn_kv* kv)
     v.seq_lens = kv->seq_lens;
     v.n_max = kv->n_max;
     v.max_pages_per_seq = kv->max_pages_per_seq;
-    v.n_kv_heads = ctx->cfg.n_kv_heads;
+    v.n_kv_heads = n_kv_heads;
     return v;
 }
+
+ha::KvView view_of(const hashattn_ctx* ctx, const hashattn_kv* kv) { return view_of(ctx->cfg.n_kv_heads, kv); }
 
 // Tokens per wave unit of SCORE/TOPK: small units fill the chip at short contexts, larger ones
 // keep the number of blocks (and of per-block tables every block has to sum) down at long contexts.
@@ -157,9 +169,10 @@ int pick_unit_tokens(const hashattn_ctx* ctx, int batch, int max_seq_len, bool m
 // (sequence, head) pairs that share the launch.  About a thousand blocks fill the chip; pieces of
 // at most `max_chunk` tokens keep a batch of mixed lengths balanced (the grid is sized by the
 // longest list, blocks past the end of a shorter one exit at once).
-void pick_splits(const hashattn_ctx* ctx, int64_t lanes, int64_t total, int batch, int64_t max_chunk, int* chunk, int* n_splits)
+void pick_splits(int64_t part_floats, int n_q_heads, int64_t lanes, int64_t total, int batch, int64_t max_chunk, int* chunk,
+                 int* n_splits)
 {
-    int64_t cap = ctx->part_floats / ((int64_t)batch * ctx->cfg.n_q_heads * ha::kPartStride);
+    int64_t cap = part_floats / ((int64_t)batch * n_q_heads * ha::kPartStride);
     if (cap > kMaxSplits) cap = kMaxSplits;
     if (cap < 1) cap = 1;
     const int64_t target = 1024, min_chunk = 64;
@@ -180,6 +193,19 @@ void pick_splits(const hashattn_ctx* ctx, int64_t lanes, int64_t total, int batc
 hashattn_status hip_fail(hashattn_ctx* ctx, hipError_t e, const char* what)
 {
     return fail(ctx, HASHATTN_HIP_ERROR, "%s: %s", what, hipGetErrorString(e));
+}
+
+// An append launch found its block counter in a state that no completed launch leaves behind (see
+// finish_append) and said so in pinned host memory: the sequence lengths of the caches it served may be
+// wrong, so every later call on the context is refused.
+hashattn_status check_append_state(hashattn_ctx* ctx, const char* what)
+{
+    const int32_t seen = *static_cast<volatile int32_t*>(ctx->append_fault_host);
+    if (seen == 0) return HASHATTN_OK;
+    return fail(ctx, HASHATTN_HIP_ERROR,
+                "%s: an earlier decode-time append counted block number %d, beyond its grid: a launch before it did "
+                "not run to its end and sequence lengths may not have advanced once; destroy this context and check the caches",
+                what, seen);
 }
 
 }  // namespace
@@ -238,12 +264,15 @@ hashattn_status hashattn_create(hashattn_ctx** out, const hashattn_config* cfg)
         (e = hipMalloc(reinterpret_cast<void**>(&ctx->frags), ctx->frag_bytes)) != hipSuccess ||
         (e = hipMalloc(reinterpret_cast<void**>(&ctx->append_done), 256)) != hipSuccess ||
         (e = hipMemset(ctx->append_done, 0, 256)) != hipSuccess ||
+        (e = hipHostMalloc(reinterpret_cast<void**>(&ctx->append_fault_host), 64, hipHostMallocMapped)) != hipSuccess ||
+        (e = hipHostGetDevicePointer(reinterpret_cast<void**>(&ctx->append_fault_dev), ctx->append_fault_host, 0)) != hipSuccess ||
         (e = hipDeviceSynchronize()) != hipSuccess) {      // the counter is zero before any stream uses it
         const long long wanted = (long long)ctx->scratch_bytes;
         hashattn_destroy(ctx);
         return fail(nullptr, HASHATTN_HIP_ERROR, "create: allocating %lld scratch bytes: %s", wanted, hipGetErrorString(e));
     }
-    if ((e = ha::setup_encode_mfma()) != hipSuccess) {
+    *ctx->append_fault_host = 0;
+    if ((e = ha::setup_encode_bulk()) != hipSuccess || (e = ha::setup_encode_mfma()) != hipSuccess) {
         hashattn_destroy(ctx);
         return fail(nullptr, HASHATTN_HIP_ERROR, "create: raising the LDS limit of the key encoder: %s", hipGetErrorString(e));
     }
@@ -262,6 +291,7 @@ hashattn_status hashattn_destroy(hashattn_ctx* ctx)
     if (ctx->part) (void)hipFree(ctx->part);
     if (ctx->frags) (void)hipFree(ctx->frags);
     if (ctx->append_done) (void)hipFree(ctx->append_done);
+    if (ctx->append_fault_host) (void)hipHostFree(ctx->append_fault_host);
     delete ctx;
     return HASHATTN_OK;
 }
@@ -270,11 +300,20 @@ const char* hashattn_last_error(const hashattn_ctx* ctx) { return ctx ? ctx->err
 
 int64_t hashattn_scratch_bytes(const hashattn_ctx* ctx) { return ctx ? ctx->scratch_bytes : 0; }
 
+hashattn_status hashattn_selftest_set_append_counter(hashattn_ctx* ctx, int32_t value, void* stream)
+{
+    if (!ctx) return HASHATTN_INVALID_ARG;
+    if (value < 0) return fail(ctx, HASHATTN_INVALID_ARG, "selftest_set_append_counter: value %d < 0", value);
+    const hipError_t e = ha::launch_set_append_counter(ctx->append_done, (uint32_t)value, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HASHATTN_OK : hip_fail(ctx, e, "selftest_set_append_counter");
+}
+
 hashattn_status hashattn_encode_keys(hashattn_ctx* ctx, const hashattn_mlp* phi_kv, const void* k_new,
                                      const void* v_new, int32_t batch, int64_t n_new, hashattn_kv* cache,
                                      void* stream)
 {
     if (!ctx) return HASHATTN_INVALID_ARG;
+    if (hashattn_status s = check_append_state(ctx, "encode_keys")) return s;
     if (hashattn_status s = check_mlp(ctx, phi_kv, ctx->cfg.n_kv_heads, "encode_keys")) return s;
     if (hashattn_status s = check_cache(ctx, cache, batch, true, "encode_keys")) return s;
     if ((k_new == nullptr) != (v_new == nullptr))
@@ -290,7 +329,8 @@ hashattn_status hashattn_encode_keys(hashattn_ctx* ctx, const hashattn_mlp* phi_
         if ((int64_t)cache->max_seq_len + n_new > ctx->cfg.max_context)
             return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "encode_keys: append would exceed max_context %lld", (long long)ctx->cfg.max_context);
     }
-    const ha::EncodeScratch enc{ctx->frags, ha::encode_mfma_scratch_bytes_per_head() / 16, ctx->append_done};
+    const ha::EncodeScratch enc{ctx->frags, ha::encode_mfma_scratch_bytes_per_head() / 16, ctx->append_done,
+                                ctx->append_fault_dev};
     const hipError_t e = ha::launch_encode_keys(view_of(phi_kv), view_of(ctx, cache), paged,
                                                 static_cast<const uint16_t*>(k_new), static_cast<const uint16_t*>(v_new),
                                                 batch, n_new, cache->max_seq_len, &enc, static_cast<hipStream_t>(stream));
@@ -303,6 +343,7 @@ hashattn_status hashattn_encode_query(hashattn_ctx* ctx, const hashattn_mlp* phi
                                       uint32_t* q_codes, void* stream)
 {
     if (!ctx) return HASHATTN_INVALID_ARG;
+    if (hashattn_status s = check_append_state(ctx, "encode_query")) return s;
     if (hashattn_status s = check_mlp(ctx, phi_q, ctx->cfg.n_q_heads, "encode_query")) return s;
     if (!q || !q_codes) return fail(ctx, HASHATTN_INVALID_ARG, "encode_query: q or q_codes is NULL");
     if (!aligned(q, 16) || !aligned(q_codes, 4)) return fail(ctx, HASHATTN_INVALID_ARG, "encode_query: q needs 16-byte, q_codes 4-byte alignment");
@@ -319,6 +360,7 @@ hashattn_status hashattn_score_topk_window(hashattn_ctx* ctx, const uint32_t* q_
                                            void* stream)
 {
     if (!ctx) return HASHATTN_INVALID_ARG;
+    if (hashattn_status s = check_append_state(ctx, "score_topk")) return s;
     if (hashattn_status s = check_cache(ctx, cache, batch, true, "score_topk")) return s;
     if (!q_codes || !idx || !count) return fail(ctx, HASHATTN_INVALID_ARG, "score_topk: q_codes, idx or count is NULL");
     if (!aligned(q_codes, 4) || !aligned(idx, 4) || !aligned(count, 4) || (k_per_seq && !aligned(k_per_seq, 4)))
@@ -353,6 +395,7 @@ hashattn_status hashattn_gather_attend(hashattn_ctx* ctx, const void* q, const h
                                        void* stream)
 {
     if (!ctx) return HASHATTN_INVALID_ARG;
+    if (hashattn_status s = check_append_state(ctx, "gather_attend")) return s;
     if (hashattn_status s = check_cache(ctx, cache, batch, false, "gather_attend")) return s;
     if (!q || !idx || !count || !out) return fail(ctx, HASHATTN_INVALID_ARG, "gather_attend: q, idx, count or out is NULL");
     if (!aligned(q, 16) || !aligned(out, 16) || !aligned(idx, 4) || !aligned(count, 4))
@@ -361,7 +404,7 @@ hashattn_status hashattn_gather_attend(hashattn_ctx* ctx, const void* q, const h
     if (k_max > ctx->cfg.max_k) return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "gather_attend: k_max %d exceeds max_k %lld", k_max, (long long)ctx->cfg.max_k);
     if (!(scale == scale)) return fail(ctx, HASHATTN_INVALID_ARG, "gather_attend: scale is NaN");
     int chunk, n_splits;
-    pick_splits(ctx, (int64_t)batch * ctx->cfg.n_q_heads, k_max, batch, 512, &chunk, &n_splits);
+    pick_splits(ctx->part_floats, ctx->cfg.n_q_heads, (int64_t)batch * ctx->cfg.n_q_heads, k_max, batch, 512, &chunk, &n_splits);
     const hipError_t e = ha::launch_gather_attend(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group,
                                                   static_cast<const uint16_t*>(q), idx, count, batch, ctx->cfg.n_q_heads,
                                                   k_max, chunk, n_splits, scale, ctx->part, static_cast<uint16_t*>(out),
@@ -373,6 +416,7 @@ hashattn_status hashattn_dense_attend(hashattn_ctx* ctx, const void* q, const ha
                                       float scale, void* out, void* stream)
 {
     if (!ctx) return HASHATTN_INVALID_ARG;
+    if (hashattn_status s = check_append_state(ctx, "dense_attend")) return s;
     if (hashattn_status s = check_cache(ctx, cache, batch, false, "dense_attend")) return s;
     if (!q || !out) return fail(ctx, HASHATTN_INVALID_ARG, "dense_attend: q or out is NULL");
     if (!aligned(q, 16) || !aligned(out, 16)) return fail(ctx, HASHATTN_INVALID_ARG, "dense_attend: q/out need 16-byte alignment");
@@ -380,7 +424,7 @@ hashattn_status hashattn_dense_attend(hashattn_ctx* ctx, const void* q, const ha
     int chunk, n_splits;
     const int64_t total = cache->max_seq_len > 0 ? cache->max_seq_len : 1;
     const int64_t lanes = (int64_t)batch * ctx->cfg.n_kv_heads;
-    pick_splits(ctx, lanes, total, batch, lanes > 128 ? 4096 : 16384, &chunk, &n_splits);   // measured on C2 / C4 shapes
+    pick_splits(ctx->part_floats, ctx->cfg.n_q_heads, lanes, total, batch, lanes > 128 ? 4096 : 16384, &chunk, &n_splits);   // measured on C2 / C4 shapes
     const hipError_t e = ha::launch_dense_attend(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group,
                                                  static_cast<const uint16_t*>(q), batch, ctx->cfg.n_q_heads,
                                                  cache->max_seq_len, chunk, n_splits, scale, ctx->part,

@@ -125,31 +125,43 @@ __device__ __forceinline__ void store_codes(const float (*a)[WD], int n_heads, i
 
 // Append mode: the sequence lengths may only move once every block has placed its rows, and a
 // separate launch for that costs more than the encoding.  Every block counts itself in after its
-// last use of seq_lens; the block that completes the count adds n_new to every length and resets
-// the counter for the next call.  Nothing a block wrote has to be visible to another one here, only
-// the counter, which is an atomic at device scope.
-__device__ __forceinline__ void finish_append(int32_t* __restrict__ done, int32_t* __restrict__ seq_lens,
-                                              int batch, int n_new)
+// last use of seq_lens; the block that completes the count adds n_new to every length.  Nothing a
+// block wrote has to be visible to another one here, only the counter, an atomic at device scope.
+// state[0] counts the blocks of all append launches of the context and is never reset; state[1] is
+// its value when the current launch began, moved on by the block that completes the launch (the next
+// launch, later in the stream, reads the new value).  So a block's number inside its launch is
+// state[0] - state[1] (modulo 2^32), and a launch that starts while an earlier one has not counted all
+// its blocks in (it did not run to its end) sees numbers beyond its grid: the block that does
+// raises `fault`, a word of pinned host memory that the C ABI reads at the start of every call on the
+// context, so the broken state is reported instead of lengths silently moving at the wrong time.
+__device__ __forceinline__ void finish_append(uint32_t* __restrict__ state, int32_t* __restrict__ fault,
+                                              int32_t* __restrict__ seq_lens, int batch, int n_new)
 {
     __shared__ int last;
     __syncthreads();                                   // all threads of the block have read seq_lens
     if (threadIdx.x == 0) {
-        const int total = gridDim.x * gridDim.y;
-        const int before = atomicAdd(done, 1);
-        last = before == total - 1;
-        if (last) *done = 0;
+        const uint32_t total = gridDim.x * gridDim.y;
+        const uint32_t base = __hip_atomic_load(state + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the base has arrived before this block counts itself in
+        const uint32_t mine = atomicAdd(state, 1u) - base;
+        last = mine == total - 1u;
+        if (last) __hip_atomic_store(state + 1, base + total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (mine >= total) __hip_atomic_store(fault, (int32_t)min(mine, 0x7fffffffu), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
     }
     __syncthreads();
     if (last)
         for (int b = threadIdx.x; b < batch; b += blockDim.x) seq_lens[b] += n_new;
 }
 
+// Test hook: leaves the append counter as a launch that stopped after `value` of its blocks would.
+__global__ void set_append_counter_kernel(uint32_t* state, uint32_t value) { state[0] = state[1] + value; }
+
 // Any supported network shape; weights are fetched inside the layer loops.
 template <int MODE, bool PAGED>
 __global__ __launch_bounds__(256) void encode_vec_kernel(MlpView phi, int n_heads, const uint16_t* __restrict__ x,
                                                          const uint16_t* __restrict__ v_new, int n_vec, int n_new,
                                                          uint32_t* __restrict__ q_codes, KvView c, int n_cap,
-                                                         int32_t* __restrict__ done)
+                                                         uint32_t* __restrict__ done, int32_t* __restrict__ fault)
 {
     __shared__ float act[2][kVecPerBlock][kMaxWidth];
     __shared__ float red[kVecPerBlock * 256];
@@ -159,7 +171,7 @@ __global__ __launch_bounds__(256) void encode_vec_kernel(MlpView phi, int n_head
     const int cur = mlp_gemv(phi, head, act, red);
     store_codes<MODE, PAGED, kMaxWidth, kVecPerBlock>(act[cur], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap,
                              phi.dims[phi.n_layers] / kBits);
-    if constexpr (MODE == 1) finish_append(done, c.seq_lens, n_vec / n_new, n_new);
+    if constexpr (MODE == 1) finish_append(done, fault, c.seq_lens, n_vec / n_new, n_new);
 }
 
 // ---- shapes known at compile time: every thread fetches all its weights of all layers up front,
@@ -212,7 +224,8 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
                                                                const uint16_t* __restrict__ x,
                                                                const uint16_t* __restrict__ v_new, int n_vec,
                                                                int n_new, uint32_t* __restrict__ q_codes,
-                                                               KvView c, int n_cap, int32_t* __restrict__ done)
+                                                               KvView c, int n_cap, uint32_t* __restrict__ done,
+                                                               int32_t* __restrict__ fault)
 {
     __shared__ float act[2][VT][kFixedWidth];
     __shared__ float red[VT * 256];
@@ -234,26 +247,27 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
     if constexpr (NL == 3)
         gemv_layer<I2, kBits, VT>(w2, phi.bias[2] ? phi.bias[2] + (int64_t)head * kBits : nullptr, act[0], act[1], red, true);
     store_codes<MODE, PAGED, kFixedWidth, VT>(act[NL & 1], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap);
-    if constexpr (MODE == 1) finish_append(done, c.seq_lens, n_vec / n_new, n_new);
+    if constexpr (MODE == 1) finish_append(done, fault, c.seq_lens, n_vec / n_new, n_new);
 }
 
 template <int MODE, bool PAGED, int NL, int D1, int D2>
 void launch_fixed(int vt, const MlpView& phi, int n_heads, const uint16_t* x, const uint16_t* v_new, int n_vec,
-                  int n_new, uint32_t* q_codes, const KvView& c, int n_cap, int32_t* done, hipStream_t stream)
+                  int n_new, uint32_t* q_codes, const KvView& c, int n_cap, uint32_t* done, int32_t* fault,
+                  hipStream_t stream)
 {
     const dim3 grid(n_heads, (n_vec + vt - 1) / vt);
     switch (vt) {
-    case 1: encode_vec_fixed_kernel<MODE, PAGED, NL, D1, D2, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done); break;
-    case 2: encode_vec_fixed_kernel<MODE, PAGED, NL, D1, D2, 2><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done); break;
-    case 4: encode_vec_fixed_kernel<MODE, PAGED, NL, D1, D2, 4><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done); break;
-    default: encode_vec_fixed_kernel<MODE, PAGED, NL, D1, D2, 8><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done); break;
+    case 1: encode_vec_fixed_kernel<MODE, PAGED, NL, D1, D2, 1><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done, fault); break;
+    case 2: encode_vec_fixed_kernel<MODE, PAGED, NL, D1, D2, 2><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done, fault); break;
+    case 4: encode_vec_fixed_kernel<MODE, PAGED, NL, D1, D2, 4><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done, fault); break;
+    default: encode_vec_fixed_kernel<MODE, PAGED, NL, D1, D2, 8><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done, fault); break;
     }
 }
 
 template <int MODE, bool PAGED>
 void launch_encode_vec(const MlpView& phi, int n_heads, const uint16_t* x, const uint16_t* v_new,
-                       int n_vec, int n_new, uint32_t* q_codes, const KvView& c, int n_cap, int32_t* done,
-                       hipStream_t stream)
+                       int n_vec, int n_new, uint32_t* q_codes, const KvView& c, int n_cap, uint32_t* done,
+                       int32_t* fault, hipStream_t stream)
 {
     const int nl = phi.n_layers, d1 = phi.dims[1], d2 = phi.dims[2];
     // vectors per block: the fewest (of 2, 4, 8; 1 for a single vector) that keep the launch within 512
@@ -262,14 +276,14 @@ void launch_encode_vec(const MlpView& phi, int n_heads, const uint16_t* x, const
     while (vt < kVecPerBlock && (int64_t)n_heads * ((n_vec + vt - 1) / vt) > 512) vt *= 2;
     const bool narrow = phi.dims[nl] == kBits;          // wider signatures take the general kernel
     if (narrow && nl == 1)
-        launch_fixed<MODE, PAGED, 1, 32, 32>(vt, phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done, stream);
+        launch_fixed<MODE, PAGED, 1, 32, 32>(vt, phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done, fault, stream);
     else if (narrow && nl == 2 && d1 == 128)
-        launch_fixed<MODE, PAGED, 2, 128, 32>(vt, phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done, stream);
+        launch_fixed<MODE, PAGED, 2, 128, 32>(vt, phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done, fault, stream);
     else if (narrow && nl == 3 && d1 == 128 && d2 == 128)
-        launch_fixed<MODE, PAGED, 3, 128, 128>(vt, phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done, stream);
+        launch_fixed<MODE, PAGED, 3, 128, 128>(vt, phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done, fault, stream);
     else {
         const dim3 grid(n_heads, (n_vec + kVecPerBlock - 1) / kVecPerBlock);
-        encode_vec_kernel<MODE, PAGED><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done);
+        encode_vec_kernel<MODE, PAGED><<<grid, 256, 0, stream>>>(phi, n_heads, x, v_new, n_vec, n_new, q_codes, c, n_cap, done, fault);
     }
 }
 
@@ -405,24 +419,38 @@ __global__ __launch_bounds__(256) void append_rows_kernel(KvView c, const uint16
         *reinterpret_cast<const uint4*>(v_new + src);
 }
 
-// LDS bytes of encode_bulk for this network; raises the kernel's dynamic LDS limit when it passes 64 KiB.
-hipError_t bulk_lds_setup(const MlpView& phi, bool paged, size_t* bytes)
+// LDS bytes of encode_bulk for this network (two tiles of the widest layer input, at most 256 wide).
+size_t bulk_lds_bytes(const MlpView& phi)
 {
     int widest = phi.dims[0];
     for (int l = 1; l < phi.n_layers; ++l) widest = widest > phi.dims[l] ? widest : phi.dims[l];
-    *bytes = sizeof(float) * 2 * kTile * (size_t)(widest + 1);
-    const void* fn = paged ? reinterpret_cast<const void*>(&encode_bulk_kernel<true>)
-                           : reinterpret_cast<const void*>(&encode_bulk_kernel<false>);
-    return hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)*bytes);
+    return sizeof(float) * 2 * kTile * (size_t)(widest + 1);
 }
 
 }  // namespace
+
+// Raises the dynamic LDS limit of the vector-unit bulk encoder to what its widest network (256-wide
+// layers) needs; called once when a context is created, never on the launch path.
+hipError_t setup_encode_bulk()
+{
+    const int bytes = (int)(sizeof(float) * 2 * kTile * (256 + 1));
+    if (hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_bulk_kernel<true>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, bytes); e != hipSuccess) return e;
+    return hipFuncSetAttribute(reinterpret_cast<const void*>(&encode_bulk_kernel<false>),
+                               hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+}
+
+hipError_t launch_set_append_counter(uint32_t* state, uint32_t value, hipStream_t stream)
+{
+    set_append_counter_kernel<<<1, 1, 0, stream>>>(state, value);
+    return hipGetLastError();
+}
 
 hipError_t launch_encode_query(const MlpView& phi, const uint16_t* q, int batch, int n_heads,
                                uint32_t* q_codes, hipStream_t stream)
 {
     KvView none{};
-    launch_encode_vec<0, false>(phi, n_heads, q, nullptr, batch, 1, q_codes, none, 0, nullptr, stream);
+    launch_encode_vec<0, false>(phi, n_heads, q, nullptr, batch, 1, q_codes, none, 0, nullptr, nullptr, stream);
     return hipGetLastError();
 }
 
@@ -432,16 +460,16 @@ hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
                               hipStream_t stream)
 {
     const int H = kv.n_kv_heads;
-    size_t lds_bytes = 0;
+    const size_t lds_bytes = bulk_lds_bytes(phi);
     const bool mfma = sc->frags && encode_mfma_supported(phi);          // bulk work goes to the matrix cores
     if (k_new) {
         if (n_new * batch <= 4 * kVecPerBlock) {
             // decode-time append: one GEMV-shaped launch writes rows and codes and moves the lengths
             const int n_vec = (int)(batch * n_new);
             if (paged)
-                launch_encode_vec<1, true>(phi, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len, sc->append_done, stream);
+                launch_encode_vec<1, true>(phi, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len, sc->append_done, sc->append_fault, stream);
             else
-                launch_encode_vec<1, false>(phi, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len, sc->append_done, stream);
+                launch_encode_vec<1, false>(phi, H, k_new, v_new, n_vec, (int)n_new, nullptr, kv, max_seq_len, sc->append_done, sc->append_fault, stream);
         } else {
             const dim3 cgrid((unsigned)((n_new * 16 + 255) / 256), H, batch);
             const dim3 egrid((unsigned)((n_new + kTile - 1) / kTile), H, batch);
@@ -450,7 +478,6 @@ hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
             if (mfma) {
                 if (hipError_t e = launch_encode_bulk_mfma(phi, kv, paged, batch, n_new, n_new, max_seq_len, 0, *sc, stream); e != hipSuccess) return e;
             } else {
-                if (hipError_t e = bulk_lds_setup(phi, paged, &lds_bytes); e != hipSuccess) return e;
                 if (paged) encode_bulk_kernel<true><<<egrid, 256, lds_bytes, stream>>>(phi, kv, max_seq_len, n_new, 0);
                 else encode_bulk_kernel<false><<<egrid, 256, lds_bytes, stream>>>(phi, kv, max_seq_len, n_new, 0);
             }
@@ -462,7 +489,6 @@ hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
             if (hipError_t e = launch_encode_bulk_mfma(phi, kv, paged, batch, span, n_new, max_seq_len, 1, *sc, stream); e != hipSuccess) return e;
         } else if (span > 0) {
             const dim3 egrid((unsigned)((span + kTile - 1) / kTile), H, batch);
-            if (hipError_t e = bulk_lds_setup(phi, paged, &lds_bytes); e != hipSuccess) return e;
             if (paged)
                 encode_bulk_kernel<true><<<egrid, 256, lds_bytes, stream>>>(phi, kv, max_seq_len, n_new, 1);
             else

@@ -22,18 +22,24 @@ hipError_t launch_encode_query(const MlpView& phi, const uint16_t* q, int batch,
                                uint32_t* q_codes, hipStream_t stream);
 
 // Scratch of the key encoders: bf16 weight fragments of every KV head for the matrix-core bulk kernel
-// (frags == nullptr: vector kernels only), and the block counter of the decode-time append (zero
-// between calls).
+// (frags == nullptr: vector kernels only), the two-word block counter of the decode-time append
+// (blocks counted so far, and that count when the current launch began) and the word of pinned host
+// memory that an append launch raises when it finds the counter in a state no completed launch
+// leaves behind.
 struct EncodeScratch {
     uint4* frags;
     int64_t quads_per_head;        // 16-byte units per head
-    int32_t* append_done;
+    uint32_t* append_done;
+    int32_t* append_fault;         // device address of the host word
 };
 
 hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
                               const uint16_t* k_new, const uint16_t* v_new,
                               int batch, int64_t n_new, int max_seq_len, const EncodeScratch* sc,
                               hipStream_t stream);
+
+hipError_t setup_encode_bulk();
+hipError_t launch_set_append_counter(uint32_t* state, uint32_t value, hipStream_t stream);
 
 int64_t encode_mfma_scratch_bytes_per_head();
 bool encode_mfma_supported(const MlpView& phi);

@@ -27,8 +27,13 @@ import workloads as W
 
 
 def measure(context: int, sparsity: int = 16, k_true: int = 32, mapping: str = "shared-projection",
-            seed: int = W.BASE_SEED + 77, heads=None, n_sink: int = 0, n_local: int = 0):
-    """Mean recall over query heads of one Llama-shaped layer (B = 1).  Returns (mean, per-head list)."""
+            seed: int = W.BASE_SEED + 77, heads=None, n_sink: int = 0, n_local: int = 0, oracle_codes: bool = False):
+    """Mean recall over query heads of one Llama-shaped layer (B = 1).  Returns (mean, per-head list).
+
+    oracle_codes: the key and query codes are computed by the oracle and uploaded (instead of the HIP
+    mapping kernels), and a third value is returned: the per-head recall of index sets computed wholly
+    by the oracle from those same codes.  SCORE + TOPK are exact integer work, so the HIP path's index
+    sets, and with them the recall, must then equal the oracle's exactly."""
     import torch
     import gpu_util as gu
 
@@ -42,21 +47,33 @@ def measure(context: int, sparsity: int = 16, k_true: int = 32, mapping: str = "
         raise ValueError(mapping)
     pitch = n_sel + n_sink + n_local
     D = gu.DeviceLayer(L, max_k=pitch)
-    D.ctx.hashattn_encode_keys(D.phi_kv, None, None, D.B, context, D.cache)
-    qc = torch.zeros((D.B, D.Hq), dtype=torch.int32, device=gu.DEV)
-    D.ctx.hashattn_encode_query(D.phi_q, D.q, D.B, qc)
+    ocache, ocodes, _ = D.oracle_cache()
+    if oracle_codes:
+        oracle.encode_keys(oracle.Mlp(L.w_kv), ocache, None, None, context)
+        oq, _ = oracle.encode_query(oracle.Mlp(L.w_q), L.q)
+        D.set_codes(ocodes)
+        qc = gu.u32_dev(oq)
+    else:
+        D.ctx.hashattn_encode_keys(D.phi_kv, None, None, D.B, context, D.cache)
+        qc = torch.zeros((D.B, D.Hq), dtype=torch.int32, device=gu.DEV)
+        D.ctx.hashattn_encode_query(D.phi_q, D.q, D.B, qc)
     idx = torch.zeros((D.B, D.Hq, pitch), dtype=torch.int32, device=gu.DEV)
     count = torch.zeros((D.B, D.Hq), dtype=torch.int32, device=gu.DEV)
     D.ctx.hashattn_score_topk_window(qc, D.cache, D.B, None, n_sel, n_sink, n_local, idx, count, None)
     torch.cuda.synchronize()
     idx_h, count_h = idx.cpu().numpy(), count.cpu().numpy()
 
-    ocache, _, _ = D.oracle_cache()
     scale = 1.0 / math.sqrt(cfg.head_dim)
-    per_head = []
+    per_head, per_head_oracle = [], []
     for h in (heads if heads is not None else range(cfg.n_q_heads)):
         truth = oracle.true_topk(ocache, 0, h // cfg.group, L.q[0, h], context, k_true, scale)
         per_head.append(oracle.recall(idx_h[0, h, :count_h[0, h]], truth))
+        if oracle_codes:
+            sc = oracle.scores(int(oq[0, h]), ocodes[0, h // cfg.group, :context])
+            chosen, _, _ = oracle.topk_window(sc, n_sel, n_sink, n_local)
+            per_head_oracle.append(oracle.recall(chosen, truth))
+    if oracle_codes:
+        return float(np.mean(per_head)), per_head, per_head_oracle
     return float(np.mean(per_head)), per_head
 
 

@@ -228,6 +228,41 @@ def test_encode_keys_append_many_heads(heads, batch):
         assert np.all(got_codes[b, :, :p0] == 0) and np.all(got_codes[b, :, p0 + 1:] == 0)
 
 
+def test_append_reports_a_counter_left_behind_by_an_unfinished_launch():
+    """The decode-time append moves the lengths from inside its kernel through a block counter that is
+    zero between calls.  With the counter set as an unfinished earlier launch would leave it, the next
+    append notices (its blocks count past the grid) and every later call on the context fails with a
+    message; a fresh context on the same cache works."""
+    import paper_2412_14468_amd as ha
+    cfg = W.scaled(W.c1(), context=300, k=16, batch=3, planted=0)
+    L = W.make_layer(cfg, seed=35)
+    D = gu.DeviceLayer(L, extra_rows=8)                 # contiguous cache with room: every row written stays inside it
+    rng = np.random.default_rng(36)
+    k_new = gu.bf16_dev(W.f32_to_bf16_bits(rng.standard_normal((3, 8, 1, 128), dtype=np.float32)))
+    v_new = gu.bf16_dev(W.f32_to_bf16_bits(rng.standard_normal((3, 8, 1, 128), dtype=np.float32)))
+    D.ctx.hashattn_encode_keys(D.phi_kv, k_new, v_new, D.B, 1, D.cache)          # a normal append: lengths move by one
+    torch.cuda.synchronize()
+    assert D.seq_lens.cpu().tolist() == [301, 301, 301]
+    D.ctx.hashattn_selftest_set_append_counter(5)
+    D.ctx.hashattn_encode_keys(D.phi_kv, k_new, v_new, D.B, 1, D.cache)          # runs to its end, reports the state
+    torch.cuda.synchronize()
+    qc = torch.zeros((D.B, D.Hq), dtype=torch.int32, device=gu.DEV)
+    with pytest.raises(ha.HashAttnError, match="block counter") as e:
+        D.ctx.hashattn_encode_query(D.phi_q, D.q, D.B, qc)
+    assert e.value.status == ha.HIP_ERROR
+    with pytest.raises(ha.HashAttnError, match="block counter"):
+        D.ctx.hashattn_encode_keys(D.phi_kv, k_new, v_new, D.B, 1, D.cache)
+    D.ctx.hashattn_selftest_set_append_counter(0)
+    D.ctx.close()
+    D.seq_lens.copy_(torch.tensor([301, 301, 301], dtype=torch.int32))
+    D.cache.max_seq_len = 301
+    ctx2 = ha.Context(D.Hq, D.Hkv, D.B, 308, 16)
+    ctx2.hashattn_encode_keys(D.phi_kv, k_new, v_new, D.B, 1, D.cache)
+    ctx2.hashattn_encode_query(D.phi_q, D.q, D.B, qc)
+    torch.cuda.synchronize()
+    assert D.seq_lens.cpu().tolist() == [302, 302, 302]
+
+
 # ---------------------------------------------------------------- whole step, Llama shape, ragged
 def run_whole_step(L, extra_rows=0, gather_heads=None):
     """Stages: GPU codes vs oracle codes; GPU TOPK on oracle codes; GPU GATHER-ATT on oracle sets;

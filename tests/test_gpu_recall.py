@@ -25,3 +25,14 @@ def test_window_never_lowers_recall():
     base, _ = rh.measure(4096, sparsity=64, k_true=32, mapping="independent-mlp", heads=heads)
     win, _ = rh.measure(4096, sparsity=64, k_true=32, mapping="independent-mlp", heads=heads, n_sink=128, n_local=128)
     assert win >= base
+
+
+@pytest.mark.parametrize("mapping,window", [("shared-projection", (0, 0)), ("independent-mlp", (0, 0)),
+                                            ("shared-projection", (128, 128))])
+def test_recall_equals_the_all_oracle_recall_on_the_oracle_codes(mapping, window):
+    """On codes computed by the oracle, the index sets of the HIP path are the oracle's, so the recall the
+    harness reports is exactly the one obtained with no GPU in the loop (not merely above a threshold)."""
+    _, per_head, per_head_oracle = rh.measure(8192, sparsity=16, k_true=32, mapping=mapping, n_sink=window[0],
+                                              n_local=window[1], oracle_codes=True)
+    assert per_head == per_head_oracle
+    assert len(per_head) == 32
