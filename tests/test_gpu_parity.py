@@ -247,10 +247,10 @@ def test_append_reports_a_counter_left_behind_by_an_unfinished_launch():
     D.ctx.hashattn_encode_keys(D.phi_kv, k_new, v_new, D.B, 1, D.cache)          # runs to its end, reports the state
     torch.cuda.synchronize()
     qc = torch.zeros((D.B, D.Hq), dtype=torch.int32, device=gu.DEV)
-    with pytest.raises(ha.HashAttnError, match="block counter") as e:
+    with pytest.raises(ha.HashAttnError, match="beyond its grid") as e:
         D.ctx.hashattn_encode_query(D.phi_q, D.q, D.B, qc)
     assert e.value.status == ha.HIP_ERROR
-    with pytest.raises(ha.HashAttnError, match="block counter"):
+    with pytest.raises(ha.HashAttnError, match="beyond its grid"):
         D.ctx.hashattn_encode_keys(D.phi_kv, k_new, v_new, D.B, 1, D.cache)
     D.ctx.hashattn_selftest_set_append_counter(0)
     D.ctx.close()
