@@ -199,6 +199,27 @@ hashattn_status hashattn_gather_attend(hashattn_ctx* ctx, const void* q,
                                        const int32_t* count, int32_t batch, int32_t k_max,
                                        float scale, void* out, void* stream);
 
+/* hashattn_gather_attend for callers that cannot allocate device memory or hold
+ * a context: code running under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  Same computation, arguments and kernels as
+ * hashattn_gather_attend, with the layer shape passed directly (n_q_heads a
+ * multiple of n_kv_heads with group size 1, 2, 4 or 8; page_size 0 or 16;
+ * head_dim 128).  The split partials go to a static device array of 8 MiB that
+ * the library holds on every GPU it runs on until the process ends; the call
+ * allocates and frees nothing (its first call on a device looks up that
+ * array's address).  Limit: batch * n_q_heads <= 15887 (one partial of 528
+ * bytes per (sequence, head) at least); beyond it the call returns
+ * HASHATTN_SCRATCH_TOO_SMALL and enqueues nothing.  All calls on one GPU share
+ * the array: calls that may overlap in time (different streams) race; calls on
+ * one stream, or ordered streams, are safe.  Nothing in the array has to be
+ * cleared between calls (every partial that is read was written by the same
+ * call).  Errors are read with hashattn_last_error(NULL) on the calling thread. */
+hashattn_status hashattn_gather_attend_noalloc(int32_t n_q_heads, int32_t n_kv_heads, int32_t page_size,
+                                               const void* q, const hashattn_kv* cache,
+                                               const int32_t* idx, const int32_t* count,
+                                               int32_t batch, int32_t k_max, float scale,
+                                               void* out, void* stream);
+
 /* Dense single-query SDPA over all seq_lens[b] tokens (section 3.1), GQA-aware
  * (K/V rows are read once per KV head).  The in-house dense decode kernel the
  * sparse path is compared against; same q/out layout as hashattn_gather_attend. */

@@ -78,6 +78,8 @@ def load() -> C.CDLL:
     L.hashattn_score_topk_window.argtypes = [vp, vp, C.POINTER(KvStruct), i32, vp, i32, i32, i32, vp, vp, vp, vp]
     L.hashattn_gather_attend.restype = i32
     L.hashattn_gather_attend.argtypes = [vp, vp, C.POINTER(KvStruct), vp, vp, i32, i32, C.c_float, vp, vp]
+    L.hashattn_gather_attend_noalloc.restype = i32
+    L.hashattn_gather_attend_noalloc.argtypes = [i32, i32, i32, vp, C.POINTER(KvStruct), vp, vp, i32, i32, C.c_float, vp, vp]
     L.hashattn_dense_attend.restype = i32
     L.hashattn_dense_attend.argtypes = [vp, vp, C.POINTER(KvStruct), i32, C.c_float, vp, vp]
     _lib = L
@@ -100,6 +102,16 @@ def _stream(stream) -> Optional[int]:
     if isinstance(stream, int):
         return stream or None
     return int(stream.cuda_stream) or None
+
+
+def hashattn_gather_attend_noalloc(n_q_heads: int, n_kv_heads: int, page_size: int, q, cache: "KvCache", idx, count,
+                                   batch: int, k_max: int, scale: float, out, stream=None) -> None:
+    """GATHER-ATT without a context: split partials live in the library's static device array."""
+    L = load()
+    st = L.hashattn_gather_attend_noalloc(n_q_heads, n_kv_heads, page_size, _ptr(q), C.byref(cache.c), _ptr(idx),
+                                          _ptr(count), batch, k_max, float(scale), _ptr(out), _stream(stream))
+    if st != OK:
+        raise HashAttnError(st, L.hashattn_last_error(None).decode())
 
 
 class Mlp:

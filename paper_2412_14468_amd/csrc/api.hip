@@ -412,6 +412,47 @@ hashattn_status hashattn_gather_attend(hashattn_ctx* ctx, const void* q, const h
     return e == hipSuccess ? HASHATTN_OK : hip_fail(ctx, e, "gather_attend");
 }
 
+hashattn_status hashattn_gather_attend_noalloc(int32_t n_q_heads, int32_t n_kv_heads, int32_t page_size, const void* q,
+                                               const hashattn_kv* cache, const int32_t* idx, const int32_t* count,
+                                               int32_t batch, int32_t k_max, float scale, void* out, void* stream)
+{
+    const char* what = "gather_attend_noalloc";
+    if (n_kv_heads < 1 || n_kv_heads > 65535 || n_q_heads < 1 || n_q_heads % n_kv_heads)
+        return fail(nullptr, HASHATTN_INVALID_ARG, "%s: n_q_heads %d must be a positive multiple of n_kv_heads %d", what, n_q_heads, n_kv_heads);
+    const int group = n_q_heads / n_kv_heads;
+    if (group != 1 && group != 2 && group != 4 && group != 8)
+        return fail(nullptr, HASHATTN_UNSUPPORTED, "%s: group size %d not in {1,2,4,8}", what, group);
+    if (page_size != 0 && page_size != ha::kPage)
+        return fail(nullptr, HASHATTN_UNSUPPORTED, "%s: page_size %d, only 0 (contiguous) or 16", what, page_size);
+    hashattn_config cfg{};
+    cfg.n_q_heads = n_q_heads; cfg.n_kv_heads = n_kv_heads; cfg.page_size = page_size;
+    cfg.max_batch = 65535; cfg.max_context = INT32_MAX;
+    if (hashattn_status s = check_cache(nullptr, cfg, cache, batch, false, what)) return s;
+    if (!q || !idx || !count || !out) return fail(nullptr, HASHATTN_INVALID_ARG, "%s: q, idx, count or out is NULL", what);
+    if (!aligned(q, 16) || !aligned(out, 16) || !aligned(idx, 4) || !aligned(count, 4))
+        return fail(nullptr, HASHATTN_INVALID_ARG, "%s: q/out need 16-byte, idx/count 4-byte alignment", what);
+    if (k_max < 1) return fail(nullptr, HASHATTN_INVALID_ARG, "%s: k_max %d < 1", what, k_max);
+    if (!(scale == scale)) return fail(nullptr, HASHATTN_INVALID_ARG, "%s: scale is NaN", what);
+    float* part = nullptr;
+    int64_t part_floats = 0;
+    if (hipError_t e = ha::static_partials(&part, &part_floats); e != hipSuccess)
+        return fail(nullptr, HASHATTN_HIP_ERROR, "%s: address of the static scratch array: %s", what, hipGetErrorString(e));
+    // one split partial per (sequence, head) is the least the split kernels need
+    const int64_t heads = (int64_t)batch * n_q_heads;
+    if (heads * ha::kPartStride > part_floats)
+        return fail(nullptr, HASHATTN_SCRATCH_TOO_SMALL,
+                    "%s: batch %d x %d query heads = %lld (sequence, head) pairs exceeds the %lld the static scratch of %lld bytes holds",
+                    what, batch, n_q_heads, (long long)heads, (long long)(part_floats / ha::kPartStride),
+                    (long long)(part_floats * (int64_t)sizeof(float)));
+    int chunk, n_splits;
+    pick_splits(part_floats, n_q_heads, heads, k_max, batch, 512, &chunk, &n_splits);
+    const hipError_t e = ha::launch_gather_attend(view_of(n_kv_heads, cache), page_size != 0, group,
+                                                  static_cast<const uint16_t*>(q), idx, count, batch, n_q_heads, k_max, chunk,
+                                                  n_splits, scale, part, static_cast<uint16_t*>(out),
+                                                  static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HASHATTN_OK : fail(nullptr, HASHATTN_HIP_ERROR, "%s: %s", what, hipGetErrorString(e));
+}
+
 hashattn_status hashattn_dense_attend(hashattn_ctx* ctx, const void* q, const hashattn_kv* cache, int32_t batch,
                                       float scale, void* out, void* stream)
 {

@@ -23,6 +23,14 @@
 #include "kernels.hpp"
 
 #include <math.h>
+#include <mutex>
+
+// Split partials of hashattn_gather_attend_noalloc, the entry point for callers that cannot allocate:
+// 8 MiB of device memory that every GPU the library runs on holds until the process ends.  Host code
+// never uses this name as an address: it asks the runtime for the array's address on the current
+// device (static_partials below) and passes that pointer to the kernels.
+constexpr int64_t kStaticPartFloats = 2 * 1024 * 1024;
+static __device__ __align__(256) float scratch[kStaticPartFloats];
 
 namespace ha {
 
@@ -431,6 +439,28 @@ __global__ __launch_bounds__(256) void merge_partials_kernel(const float* __rest
 constexpr float kLog2e = 1.4426950408889634f;
 
 }  // namespace
+
+// Address and size (in floats) of the static partials array on the current device.  The address is
+// looked up once per device (every GPU has its own copy of the array at its own address) and kept.
+hipError_t static_partials(float** ptr, int64_t* n_floats)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static float* per_device[kMaxDevices] = {};
+    int dev = 0;
+    if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(mu);
+    if (!per_device[dev]) {
+        float* p = nullptr;
+        if (hipError_t e = hipGetSymbolAddress(reinterpret_cast<void**>(&p), HIP_SYMBOL(scratch)); e != hipSuccess) return e;
+        if (!p) return hipErrorInvalidSymbol;
+        per_device[dev] = p;
+    }
+    *ptr = per_device[dev];
+    *n_floats = kStaticPartFloats;
+    return hipSuccess;
+}
 
 hipError_t launch_gather_attend(const KvView& kv, bool paged, int group, const uint16_t* q,
                                 const int32_t* idx, const int32_t* count, int batch, int n_q_heads,

@@ -78,6 +78,9 @@ hipError_t launch_gather_attend(const KvView& kv, bool paged, int group, const u
                                 int k_max, int chunk, int n_splits, float scale, float* part,
                                 uint16_t* out, hipStream_t stream);
 
+// The library's static split-partials array on the current device (for the entry point that allocates nothing).
+hipError_t static_partials(float** ptr, int64_t* n_floats);
+
 hipError_t launch_dense_attend(const KvView& kv, bool paged, int group, const uint16_t* q,
                                int batch, int n_q_heads, int max_seq_len, int chunk, int n_splits,
                                float scale, float* part, uint16_t* out, hipStream_t stream);
