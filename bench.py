@@ -363,15 +363,20 @@ def run_workload(name, args, headline):
         seconds = time_region(torch, timed, 1)
         launch = f"HIP graph of {ring} layer-steps"
     us_per_step = seconds * 1e6 / K
-    lens_final = [int(n) + (1 if cfg.append else 0) for n in layers[0].lens_host]
-    ks = [int(x) for x in layers[0].k_host]
-    if args.sink or args.local:          # tokens attended per head: always-kept ones plus the retrieved budget
-        def attended(n, kk):
-            lo = min(args.sink, n)
-            hi = max(lo, n - args.local)
-            return lo + min(kk, hi - lo) + (n - hi)
-        ks = [attended(n, kk) for n, kk in zip(lens_final, ks)]
-    alg_bytes = W.algorithmic_bytes(Hkv, Hq, d, lens_final, ks)
+    # bytes per step: the mean over the ring's layers (their lengths differ in the mixed-length workload)
+    step_new = 1 if cfg.append else 0
+
+    def attended(n, kk):
+        lo = min(args.sink, n)
+        hi = max(lo, n - args.local)
+        return lo + min(kk, hi - lo) + (n - hi)
+
+    def layer_shape(s):
+        lens = [int(n) + step_new for n in s.lens_host]
+        return lens, [attended(n, int(kk)) for n, kk in zip(lens, s.k_host)]
+    shapes = [layer_shape(s) for s in layers]
+    lens_final, ks = shapes[0]
+    alg_bytes = round(sum(W.algorithmic_bytes(Hkv, Hq, d, ln, kk) for ln, kk in shapes) / ring)
     gbs = alg_bytes / (us_per_step * 1e-6) / 1e9
 
     def stage_us(body):
@@ -393,8 +398,8 @@ def run_workload(name, args, headline):
     def encq_sweep():
         for s in layers:
             ctx.hashattn_encode_query(s.phi_q, s.q, s.B, s.q_codes)
-    gather_bytes = W.gathered_bytes(Hq, d, lens_final, ks)
-    code_bytes = 4 * Hkv * sum(lens_final)
+    gather_bytes = round(sum(W.gathered_bytes(Hq, d, ln, kk) for ln, kk in shapes) / ring)
+    code_bytes = round(sum(4 * Hkv * sum(ln) for ln, _ in shapes) / ring)
     gather_us, topk_us, encq_us = stage_us(gather_sweep), stage_us(topk_sweep), stage_us(encq_sweep)
     gather_gbs = gather_bytes / (gather_us * 1e-6) / 1e9
 
@@ -404,7 +409,7 @@ def run_workload(name, args, headline):
             for s in layers:
                 runner.dense_step(ctx, s)
         dense_us = stage_us(dense_sweep)
-        dense_bytes = sum(2 * Hkv * n * d * 2 + 2 * Hq * d * 2 for n in lens_final)
+        dense_bytes = sum(sum(2 * Hkv * n * d * 2 + 2 * Hq * d * 2 for n in ln) for ln, _ in shapes) / ring
         dense = {"us_per_layer": round(dense_us, 3), "GBps": round(dense_bytes / (dense_us * 1e-6) / 1e9, 1),
                  "speedup_sparse_vs_dense": round(dense_us / us_per_step, 3)}
 
@@ -423,7 +428,7 @@ def run_workload(name, args, headline):
         runner.build_key_codes(ctx, layers[0])
     rebuild()
     enc_us = event_time_us(torch, rebuild, 3)
-    n_vec = sum(int(n) for n in layers[0].lens_host) * Hkv
+    n_vec = sum(int(n) for n in layers[0].lens_host) * Hkv       # the rebuild is timed on ring layer 0 alone
     dims = cfg.mlp_dims
     mlp_flop = 2 * sum(a * b for a, b in zip(dims[:-1], dims[1:]))
     rec["key_encode"] = {"us": round(enc_us, 1), "Mvectors_per_s": round(n_vec / enc_us, 1),
@@ -475,6 +480,8 @@ def workload_text(r, args):
             f"k={describe_lengths(r['ks'])} ({round(sum(r['lens_final']) / max(sum(r['ks']), 1))}x sparsity), "
             f"{cfg.n_q_heads} q heads / {cfg.n_kv_heads} KV heads, d={cfg.head_dim}, "
             f"mapping MLPs {'-'.join(map(str, cfg.mlp_dims))} fp32"
+            + (" in ring layer 0 (every ring layer draws its own lengths; bytes per step are the mean over the ring)"
+               if cfg.mixed_lengths else "")
             + (", paged KV (16 tokens/page)" if cfg.page_size else "")
             + (", one-token append per step" if cfg.append else "")
             + (f", first {args.sink} and last {args.local} tokens always kept (k counts them here)"

@@ -83,7 +83,7 @@ __device__ __forceinline__ void count_chunk(const uint4 (&cw)[4], int base, int 
 template <int G, bool PAGED, int WPB>
 __global__ __launch_bounds__(WPB * kWave) void score_hist_kernel(KvView c, const uint32_t* __restrict__ q_codes,
                                                               int n_q_heads, int n_cap, int unit_tokens,
-                                                              int n_sink, int n_local,
+                                                              int n_sink, int n_local, int speculate,
                                                               int blocks_pitch, int32_t* __restrict__ blk_cum)
 {
     __shared__ __attribute__((aligned(16))) unsigned hist[G * kBins * kBinCopies];   // [head][score][copy]
@@ -103,18 +103,18 @@ __global__ __launch_bounds__(WPB * kWave) void score_hist_kernel(KvView c, const
 #pragma unroll
     for (int it = 0; it < 4; ++it) cw[it] = make_uint4(0u, 0u, 0u, 0u);     // element by element: keeps the array in registers
     // contiguous cache: rows up to the host's bound n_cap exist whatever the sequence length is, so
-    // the first loads need not wait for it (what lies past the length is masked out below)
-    if constexpr (!PAGED) {
-        if (t_begin < n_cap) load_chunk<PAGED, 4>(c, b, kvh, (int)t_begin, (int)min((int64_t)n_cap, t_begin + unit_tokens), lane, cw);
-    }
+    // the first loads need not wait for it (what lies past the length is masked out below).  Not in a
+    // batch of mixed lengths (speculate == 0): there most blocks of a short sequence lie beyond its end,
+    // and a block that has asked for codes cannot leave before they have arrived.
+    const bool early = !PAGED && speculate != 0;
+    if (early && t_begin < n_cap)
+        load_chunk<PAGED, 4>(c, b, kvh, (int)t_begin, (int)min((int64_t)n_cap, t_begin + unit_tokens), lane, cw);
     const int n = min(n_raw, n_cap);           // n_cap: the host's bound that sized grid and scratch
     if ((int64_t)bx * WPB * unit_tokens >= n) return;      // whole block beyond the sequence
     const bool active = t_begin < n;
     const int t_end = (int)min((int64_t)n, t_begin + unit_tokens);
     const int lo = min(n_sink, n), hi = max(lo, n - n_local);   // always-kept tokens [0, lo) and [hi, n) are not scored
-    if constexpr (PAGED) {
-        if (active) load_chunk<PAGED, 4>(c, b, kvh, (int)t_begin, t_end, lane, cw);
-    }
+    if (!early && active) load_chunk<PAGED, 4>(c, b, kvh, (int)t_begin, t_end, lane, cw);
     uint32_t qc[G];                                        // complemented (see count_chunk); made uniform after the
 #pragma unroll                                             // complement so that it stays one
     for (int j = 0; j < G; ++j) qc[j] = (uint32_t)uniform(~qraw[j]);
@@ -221,7 +221,7 @@ __device__ __forceinline__ void to_lane_runs(const uint4 (&cw)[NIT], uint4* stag
 template <int G, bool PAGED, int NIT, int NCH, int WPB>
 __global__ __launch_bounds__(WPB * kWave) void topk_select_kernel(KvView c, const uint32_t* __restrict__ q_codes,
                                                                const int32_t* __restrict__ k_per_seq, int k_max,
-                                                               int n_sink, int n_local, int pitch,
+                                                               int n_sink, int n_local, int pitch, int speculate,
                                                                int n_q_heads, int n_cap, int blocks_pitch,
                                                                const int32_t* __restrict__ blk_cum,
                                                                int32_t* __restrict__ idx, int32_t* __restrict__ count,
@@ -243,9 +243,13 @@ __global__ __launch_bounds__(WPB * kWave) void topk_select_kernel(KvView c, cons
     const int64_t bh0 = (int64_t)b * n_q_heads + kvh * G;
     const int nb_cap = gridDim.x;                              // blocks the host launched per sequence
 
-    // ---- everything that does not depend on another load is requested first
+    // ---- everything that does not depend on another load is requested first; in a batch of mixed
+    // lengths (speculate == 0) the length comes before that, over the scalar path, so that a block
+    // beyond the end of a short sequence leaves without waiting for anything else
     const int n_raw = c.seq_lens[b];
     const int k_raw = k_per_seq ? k_per_seq[b] : k_max;
+    constexpr int kBlockTokensEarly = 4 * NIT * kWave * NCH * WPB;
+    if (!speculate && bx > 0 && (int64_t)bx * kBlockTokensEarly >= min(n_raw, n_cap)) return;
     const int srow = tid / kCumRow, scol = tid - srow * kCumRow;
     constexpr int kPrefetch = 3;                                // passes of table rows requested up front
     int tv[G][kPrefetch];
@@ -266,9 +270,9 @@ __global__ __launch_bounds__(WPB * kWave) void topk_select_kernel(KvView c, cons
     uint4 cw[NIT];
 #pragma unroll
     for (int it = 0; it < NIT; ++it) cw[it] = make_uint4(0u, 0u, 0u, 0u);   // element by element: keeps the array in registers
-    if constexpr (!PAGED) {          // contiguous cache: no need to wait for the sequence length (see score_hist)
-        if (t_begin < n_cap) load_chunk<PAGED, NIT>(c, b, kvh, (int)t_begin, (int)min((int64_t)n_cap, t_begin + kUnitTokens), lane, cw);
-    }
+    const bool early = !PAGED && speculate != 0;     // contiguous cache: no need to wait for the sequence length (see score_hist)
+    if (early && t_begin < n_cap)
+        load_chunk<PAGED, NIT>(c, b, kvh, (int)t_begin, (int)min((int64_t)n_cap, t_begin + kUnitTokens), lane, cw);
     uint32_t qc[G];
 #pragma unroll
     for (int j = 0; j < G; ++j) qc[j] = (uint32_t)uniform(qraw[j]);
@@ -283,9 +287,7 @@ __global__ __launch_bounds__(WPB * kWave) void topk_select_kernel(KvView c, cons
     const int n_blocks = (n + kBlockTokens - 1) / kBlockTokens;
     const bool active = t_begin < n && !nothing;
     const int t_end = (int)min((int64_t)n, t_begin + kUnitTokens);
-    if constexpr (PAGED) {
-        if (active) load_chunk<PAGED, NIT>(c, b, kvh, (int)t_begin, t_end, lane, cw);
-    }
+    if (!early && active) load_chunk<PAGED, NIT>(c, b, kvh, (int)t_begin, t_end, lane, cw);
     __syncthreads();
 
     // ---- cumulative counts per head from the per-block rows, in one trip to memory: over the whole
@@ -459,7 +461,8 @@ hipError_t select_variant(bool setup_only, const KvView& kv, const TopkCall& a, 
         return hipFuncSetAttribute(reinterpret_cast<const void*>(&topk_select_kernel<G, PAGED, NIT, NCH, WPB>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     topk_select_kernel<G, PAGED, NIT, NCH, WPB><<<grid, dim3(WPB * kWave), lds, stream>>>(
-        kv, a.q_codes, a.k_per_seq, a.k_max, a.n_sink, a.n_local, a.k_max + a.n_sink + a.n_local, a.n_q_heads,
+        kv, a.q_codes, a.k_per_seq, a.k_max, a.n_sink, a.n_local, a.k_max + a.n_sink + a.n_local,
+        a.k_per_seq == nullptr, a.n_q_heads,
         a.max_seq_len, sc.blocks_pitch, sc.blk_cum, a.idx, a.count, a.threshold);
     return hipSuccess;
 }
@@ -490,8 +493,10 @@ hipError_t launch_gpw(bool setup_only, const KvView& kv, const TopkCall& a, int 
     int n_blocks = (int)((a.max_seq_len + block_tokens - 1) / block_tokens);
     if (n_blocks < 1) n_blocks = 1;               // block 0 of every group still reports count = 0
     const dim3 grid(n_blocks, kv.n_kv_heads, a.batch), block(WPB * kWave);
+    // a k per sequence means lengths differ: blocks then wait for their sequence's length before any other load
     score_hist_kernel<G, PAGED, WPB><<<grid, block, 0, stream>>>(kv, a.q_codes, a.n_q_heads, a.max_seq_len, unit_tokens,
-                                                             a.n_sink, a.n_local, sc.blocks_pitch, sc.blk_cum);
+                                                             a.n_sink, a.n_local, a.k_per_seq == nullptr, sc.blocks_pitch,
+                                                             sc.blk_cum);
     if (hipError_t e = select_by_unit<G, PAGED, WPB>(false, unit_tokens, kv, a, sc, grid, stream); e != hipSuccess) return e;
     return hipGetLastError();
 }
