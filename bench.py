@@ -83,11 +83,15 @@ def workload_config(name):
     return make(W), ring
 
 
-def device_layer_synthetic(cfg, seed):
-    """One ring layer drawn on the device by the recipe of workloads.device_tensors."""
+def device_layer_synthetic(cfg, seed, lens_view=None):
+    """One ring layer drawn on the device by the recipe of workloads.device_tensors.  lens_view: where the
+    layer's sequence lengths live (a row of one tensor for the whole ring), if given."""
     import workloads as W
     from paper_2412_14468_amd.runner import layer_from_tensors
     t = W.device_tensors(cfg, seed)
+    if lens_view is not None:
+        lens_view.copy_(t["seq_lens"])
+        t["seq_lens"] = lens_view
     s = layer_from_tensors(t)
     s.lens_host, s.k_host = t["seq_lens_host"], t["k_per_seq_host"]
     return s
@@ -315,7 +319,10 @@ def run_workload(name, args, headline):
     B, Hq, Hkv, d = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
 
     t_setup = time.perf_counter()
-    layers = [device_layer_synthetic(cfg, W.BASE_SEED + 1000 * cfg.index + i) for i in range(ring)]
+    # the sequence lengths of all ring layers sit in one tensor, so that an append workload puts them back
+    # to "N - 1 tokens cached" with one small copy per sweep over the ring
+    lens_all = torch.zeros((ring, B), dtype=torch.int32, device=DEV)
+    layers = [device_layer_synthetic(cfg, W.BASE_SEED + 1000 * cfg.index + i, lens_all[i]) for i in range(ring)]
     n_cap = max(int(s.k.shape[2]) if s.page_table is None else int(s.page_table.shape[1]) * cfg.page_size for s in layers)
     k_max = max(s.k_max for s in layers)
     ctx = ha.Context(Hq, Hkv, B, n_cap, k_max + args.sink + args.local, page_size=cfg.page_size)
@@ -325,6 +332,7 @@ def run_workload(name, args, headline):
         runner.build_key_codes(ctx, s)
         s.lens0_dev = s.seq_lens.clone()
         s.max_len0 = s.cache.max_seq_len
+    lens0_all = lens_all.clone()
     torch.cuda.synchronize()
     t_setup = time.perf_counter() - t_setup
     if headline and args.calibration_copy:
@@ -334,13 +342,14 @@ def run_workload(name, args, headline):
         del src
 
     def one_step(s):
-        if cfg.append:                       # every step appends to a cache that holds N - 1 tokens (the copy is timed too)
-            s.seq_lens.copy_(s.lens0_dev)
+        if cfg.append:                       # every step appends to a cache that holds N - 1 tokens
             s.cache.max_seq_len = s.max_len0
         runner.decode_step(ctx, s, append=cfg.append)
 
     def sweep(n_steps, start=0):
         for i in range(n_steps):
+            if cfg.append and (i == 0 or (start + i) % ring == 0):
+                lens_all.copy_(lens0_all)    # one copy of ring x B lengths per sweep (timed with the steps)
             one_step(layers[(start + i) % ring])
 
     # ---- whole-step timing: W warm-up steps, then exactly K timed steps

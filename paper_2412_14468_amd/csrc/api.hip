@@ -404,7 +404,12 @@ hashattn_status hashattn_gather_attend(hashattn_ctx* ctx, const void* q, const h
     if (k_max > ctx->cfg.max_k) return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "gather_attend: k_max %d exceeds max_k %lld", k_max, (long long)ctx->cfg.max_k);
     if (!(scale == scale)) return fail(ctx, HASHATTN_INVALID_ARG, "gather_attend: scale is NaN");
     int chunk, n_splits;
-    pick_splits(ctx->part_floats, ctx->cfg.n_q_heads, (int64_t)batch * ctx->cfg.n_q_heads, k_max, batch, 512, &chunk, &n_splits);
+    // pieces of at most 512 rows; twice that measured 2 % faster with many lists of equal length (16 sequences
+    // of 131072 tokens) and 3 % slower on a paged batch of mixed lengths, where it leaves too few pieces
+    // to balance, so paged caches keep 512
+    const int64_t lists = (int64_t)batch * ctx->cfg.n_q_heads;
+    const int64_t max_rows = lists >= 256 && ctx->cfg.page_size == 0 ? 1024 : 512;
+    pick_splits(ctx->part_floats, ctx->cfg.n_q_heads, lists, k_max, batch, max_rows, &chunk, &n_splits);
     const hipError_t e = ha::launch_gather_attend(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group,
                                                   static_cast<const uint16_t*>(q), idx, count, batch, ctx->cfg.n_q_heads,
                                                   k_max, chunk, n_splits, scale, ctx->part, static_cast<uint16_t*>(out),

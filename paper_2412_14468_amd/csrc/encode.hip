@@ -134,14 +134,21 @@ __device__ __forceinline__ void store_codes(const float (*a)[WD], int n_heads, i
 // its blocks in (it did not run to its end) sees numbers beyond its grid: the block that does
 // raises `fault`, a word of pinned host memory that the C ABI reads at the start of every call on the
 // context, so the broken state is reported instead of lengths silently moving at the wrong time.
-__device__ __forceinline__ void finish_append(uint32_t* __restrict__ state, int32_t* __restrict__ fault,
+// state[1] only changes once every block of the launch has counted itself in, so a block may read it
+// at any time before it does so itself: append_base() asks for it when the kernel starts, and the
+// value has long arrived when finish_append() needs it (one trip to memory less at the block's end).
+__device__ __forceinline__ uint32_t append_base(const uint32_t* __restrict__ state)
+{
+    return __hip_atomic_load(state + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ void finish_append(uint32_t* __restrict__ state, uint32_t base, int32_t* __restrict__ fault,
                                               int32_t* __restrict__ seq_lens, int batch, int n_new)
 {
     __shared__ int last;
     __syncthreads();                                   // all threads of the block have read seq_lens
     if (threadIdx.x == 0) {
         const uint32_t total = gridDim.x * gridDim.y;
-        const uint32_t base = __hip_atomic_load(state + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the base has arrived before this block counts itself in
         const uint32_t mine = atomicAdd(state, 1u) - base;
         last = mine == total - 1u;
@@ -166,12 +173,14 @@ __global__ __launch_bounds__(256) void encode_vec_kernel(MlpView phi, int n_head
     __shared__ float act[2][kVecPerBlock][kMaxWidth];
     __shared__ float red[kVecPerBlock * 256];
     const int head = blockIdx.x, v0 = blockIdx.y * kVecPerBlock;
+    uint32_t base = 0;
+    if constexpr (MODE == 1) base = append_base(done);
     load_vectors<MODE, kMaxWidth, kVecPerBlock>(act[0], n_heads, head, v0, x, n_vec, n_new);
     __syncthreads();
     const int cur = mlp_gemv(phi, head, act, red);
     store_codes<MODE, PAGED, kMaxWidth, kVecPerBlock>(act[cur], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap,
                              phi.dims[phi.n_layers] / kBits);
-    if constexpr (MODE == 1) finish_append(done, fault, c.seq_lens, n_vec / n_new, n_new);
+    if constexpr (MODE == 1) finish_append(done, base, fault, c.seq_lens, n_vec / n_new, n_new);
 }
 
 // ---- shapes known at compile time: every thread fetches all its weights of all layers up front,
@@ -230,6 +239,8 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
     __shared__ float act[2][VT][kFixedWidth];
     __shared__ float red[VT * 256];
     const int head = blockIdx.x, v0 = blockIdx.y * VT;
+    uint32_t base = 0;
+    if constexpr (MODE == 1) base = append_base(done);
     constexpr int O0 = NL == 1 ? kBits : D1;            // outputs of layer 0
     constexpr int I1 = D1, O1 = NL == 2 ? kBits : D2;   // layer 1 (NL >= 2)
     constexpr int I2 = D2;                              // layer 2 (NL == 3), 32 outputs
@@ -247,7 +258,7 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
     if constexpr (NL == 3)
         gemv_layer<I2, kBits, VT>(w2, phi.bias[2] ? phi.bias[2] + (int64_t)head * kBits : nullptr, act[0], act[1], red, true);
     store_codes<MODE, PAGED, kFixedWidth, VT>(act[NL & 1], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap);
-    if constexpr (MODE == 1) finish_append(done, fault, c.seq_lens, n_vec / n_new, n_new);
+    if constexpr (MODE == 1) finish_append(done, base, fault, c.seq_lens, n_vec / n_new, n_new);
 }
 
 template <int MODE, bool PAGED, int NL, int D1, int D2>
