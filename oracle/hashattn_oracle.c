@@ -7,7 +7,7 @@
  *   - SCORE    Hamming distance as bitcount(xor) (section 4.1, eq. 1 and the
  *              "Implementation" paragraph); used as the similarity 32 - H,
  *              which orders tokens exactly as -H does
- *   - TOPK     "standard top-k on these scores" (section 4); optionally with the first and most
+ *   - TOPK     the k best scores, by an ordinary top-k (section 4); optionally with the first and most
  *              recent tokens always kept and the budget counting only retrieved tokens (section 5)
  *   - GATHER-ATT  softmax attention restricted to the index set (section 4)
  *   - SDPA     single-query dense attention (section 3.1)
