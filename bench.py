@@ -72,6 +72,9 @@ def parse_args():
                     help="also time SCORE + TOPK alone on uniform random codes of 32..512 bits at this workload's shape")
     ap.add_argument("--sink", type=int, default=0, help="always keep this many first tokens (k counts the rest)")
     ap.add_argument("--local", type=int, default=0, help="always keep this many most recent tokens")
+    ap.add_argument("--planted", type=int, default=-1,
+                    help="planted pivotal tokens per query head (default: the workload's 64); 0 skips them, which leaves "
+                         "every byte count unchanged and is used for counter runs under rocprofv3, to keep set-up short")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (reference for scaling rocprofv3 byte counters)")
     return ap.parse_args()
@@ -315,6 +318,8 @@ def run_workload(name, args, headline):
     import workloads as W
 
     cfg, ring_default = workload_config(name)
+    if args.planted >= 0:
+        cfg = W.scaled(cfg, planted=args.planted)
     ring = (args.ring if headline else 0) or ring_default
     B, Hq, Hkv, d = cfg.batch, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim
 
