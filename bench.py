@@ -364,18 +364,22 @@ def run_workload(name, args, headline):
         seconds = time_region(torch, lambda: sweep(K), 1)
         launch = "eager launches"
     else:
+        # the K timed steps are as few graph launches as possible (one for K <= 256): a launch costs a few
+        # microseconds of idle GPU, which would count against a short run
         full = capture(torch, lambda: sweep(ring))
-        rem_k = capture(torch, lambda: sweep(K % ring)) if K % ring else None
+        chunk = min(K, max(ring, 256 // ring * ring))
+        g_chunk = full if chunk == ring else capture(torch, lambda: sweep(chunk))
+        g_rem = capture(torch, lambda: sweep(K % chunk)) if K % chunk else None
         for _ in range(max(1, (Wm + ring - 1) // ring)):
             full()
 
         def timed():
-            for _ in range(K // ring):
-                full()
-            if rem_k:
-                rem_k()
+            for _ in range(K // chunk):
+                g_chunk()
+            if g_rem:
+                g_rem()
         seconds = time_region(torch, timed, 1)
-        launch = f"HIP graph of {ring} layer-steps"
+        launch = f"HIP graphs of {chunk} layer-steps over a ring of {ring} layers"
     us_per_step = seconds * 1e6 / K
     # bytes per step: the mean over the ring's layers (their lengths differ in the mixed-length workload)
     step_new = 1 if cfg.append else 0
