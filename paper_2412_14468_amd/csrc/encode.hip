@@ -87,12 +87,37 @@ __device__ __forceinline__ void load_vectors(float (*act0)[WD], int n_heads, int
     }
 }
 
+// Cache position of the row this thread will place (MODE 1; same thread-to-vector mapping as store_codes):
+// the sequence's length plus the row's number among the appended ones.  Asked for when the kernel
+// starts, so that the block can count itself in (finish_append) long before it has finished computing.
+template <int VB>
+__device__ __forceinline__ int append_position(const KvView& c, int v0, int n_vec, int n_new, int n_cap)
+{
+    const int slot = threadIdx.x >> 5, v = min(slot, VB - 1), vec = v0 + v;
+    if (slot >= VB || vec >= n_vec) return 0;
+    const int b = vec / n_new;
+    return min(c.seq_lens[b], n_cap) + (vec - b * n_new);
+}
+
+// The 16 bytes of the new K row (threads 0..15 of a vector's 32) or V row (16..31) that this thread
+// copies into the cache in store_codes, also requested when the kernel starts.
+template <int VB>
+__device__ __forceinline__ uint4 append_piece(const uint16_t* __restrict__ k_new, const uint16_t* __restrict__ v_new,
+                                              int n_heads, int head, int v0, int n_vec, int n_new)
+{
+    const int slot = threadIdx.x >> 5, j = threadIdx.x & 31, v = min(slot, VB - 1), vec = v0 + v;
+    if (slot >= VB || vec >= n_vec) return make_uint4(0u, 0u, 0u, 0u);
+    const int b = vec / n_new, jn = vec - b * n_new;
+    const int64_t src = ((int64_t)b * n_heads + head) * n_new + jn;
+    return *(reinterpret_cast<const uint4*>((j < 16 ? k_new : v_new) + src * kHeadDim) + (j & 15));
+}
+
 // a: [VB][WD] pre-sign activations of the last layer of the block's VB vectors
 template <int MODE, bool PAGED, int WD, int VB>
 __device__ __forceinline__ void store_codes(const float (*a)[WD], int n_heads, int head, int v0,
                                             const uint16_t* __restrict__ x, const uint16_t* __restrict__ v_new,
                                             int n_vec, int n_new, uint32_t* __restrict__ q_codes,
-                                            const KvView& c, int n_cap, int words = 1)
+                                            const KvView& c, int pos, const uint4& piece, int words = 1)
 {
     // thread (v = tid / 32, j = tid % 32) owns bit j of every code word of vector v (unit 32 w + j of
     // word w); a wave ballot packs one word of two vectors
@@ -102,7 +127,7 @@ __device__ __forceinline__ void store_codes(const float (*a)[WD], int n_heads, i
     const int b = MODE == 0 ? vec : vec / n_new, jn = MODE == 0 ? 0 : vec - b * n_new;
     int64_t row = 0;
     if constexpr (MODE == 1) {
-        if (live) row = row_of<PAGED>(c, b, head, min(c.seq_lens[b], n_cap) + jn);
+        if (live) row = row_of<PAGED>(c, b, head, pos);        // pos: this thread's value of append_position()
     }
     for (int w = 0; w < words; ++w) {
         const uint64_t mask = __ballot(a[v][32 * w + j] > 0.f);
@@ -114,19 +139,18 @@ __device__ __forceinline__ void store_codes(const float (*a)[WD], int n_heads, i
     }
     if (live) {
         if constexpr (MODE == 1) {
-            const int64_t src = ((int64_t)b * n_heads + head) * n_new + jn;
-            // 32 threads copy the 256-byte K row and V row, 16 bytes each (16 + 16 threads)
-            const uint4* from = reinterpret_cast<const uint4*>((j < 16 ? x : v_new) + src * kHeadDim) + (j & 15);
+            // 32 threads copy the 256-byte K row and V row, 16 bytes each (16 + 16 threads; see append_piece)
             uint4* to = reinterpret_cast<uint4*>(const_cast<uint16_t*>(j < 16 ? c.k : c.v) + row * kHeadDim) + (j & 15);
-            *to = *from;
+            *to = piece;
         }
     }
 }
 
-// Append mode: the sequence lengths may only move once every block has placed its rows, and a
-// separate launch for that costs more than the encoding.  Every block counts itself in after its
-// last use of seq_lens; the block that completes the count adds n_new to every length.  Nothing a
-// block wrote has to be visible to another one here, only the counter, an atomic at device scope.
+// Append mode: the sequence lengths may only move once every block has read them, and a separate
+// launch for that costs more than the encoding.  Every block reads the lengths it needs when it
+// starts (append_position) and counts itself in right after; the block that completes the count adds
+// n_new to every length, as a rule while the others are still computing.  Nothing a block wrote has
+// to be visible to another one here, only the counter, an atomic at device scope.
 // state[0] counts the blocks of all append launches of the context and is never reset; state[1] is
 // its value when the current launch began, moved on by the block that completes the launch (the next
 // launch, later in the stream, reads the new value).  So a block's number inside its launch is
@@ -135,8 +159,7 @@ __device__ __forceinline__ void store_codes(const float (*a)[WD], int n_heads, i
 // raises `fault`, a word of pinned host memory that the C ABI reads at the start of every call on the
 // context, so the broken state is reported instead of lengths silently moving at the wrong time.
 // state[1] only changes once every block of the launch has counted itself in, so a block may read it
-// at any time before it does so itself: append_base() asks for it when the kernel starts, and the
-// value has long arrived when finish_append() needs it (one trip to memory less at the block's end).
+// at any time before it does so itself: append_base() asks for it together with the lengths.
 __device__ __forceinline__ uint32_t append_base(const uint32_t* __restrict__ state)
 {
     return __hip_atomic_load(state + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -146,10 +169,10 @@ __device__ __forceinline__ void finish_append(uint32_t* __restrict__ state, uint
                                               int32_t* __restrict__ seq_lens, int batch, int n_new)
 {
     __shared__ int last;
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's length (and the base) have arrived
     __syncthreads();                                   // all threads of the block have read seq_lens
     if (threadIdx.x == 0) {
         const uint32_t total = gridDim.x * gridDim.y;
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // the base has arrived before this block counts itself in
         const uint32_t mine = atomicAdd(state, 1u) - base;
         last = mine == total - 1u;
         if (last) __hip_atomic_store(state + 1, base + total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -173,14 +196,19 @@ __global__ __launch_bounds__(256) void encode_vec_kernel(MlpView phi, int n_head
     __shared__ float act[2][kVecPerBlock][kMaxWidth];
     __shared__ float red[kVecPerBlock * 256];
     const int head = blockIdx.x, v0 = blockIdx.y * kVecPerBlock;
-    uint32_t base = 0;
-    if constexpr (MODE == 1) base = append_base(done);
+    int pos = 0;
+    uint4 piece = make_uint4(0u, 0u, 0u, 0u);
+    if constexpr (MODE == 1) {
+        const uint32_t base = append_base(done);
+        pos = append_position<kVecPerBlock>(c, v0, n_vec, n_new, n_cap);
+        piece = append_piece<kVecPerBlock>(x, v_new, n_heads, head, v0, n_vec, n_new);
+        finish_append(done, base, fault, c.seq_lens, n_vec / n_new, n_new);
+    }
     load_vectors<MODE, kMaxWidth, kVecPerBlock>(act[0], n_heads, head, v0, x, n_vec, n_new);
     __syncthreads();
     const int cur = mlp_gemv(phi, head, act, red);
-    store_codes<MODE, PAGED, kMaxWidth, kVecPerBlock>(act[cur], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap,
-                             phi.dims[phi.n_layers] / kBits);
-    if constexpr (MODE == 1) finish_append(done, base, fault, c.seq_lens, n_vec / n_new, n_new);
+    store_codes<MODE, PAGED, kMaxWidth, kVecPerBlock>(act[cur], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, pos,
+                             piece, phi.dims[phi.n_layers] / kBits);
 }
 
 // ---- shapes known at compile time: every thread fetches all its weights of all layers up front,
@@ -239,8 +267,6 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
     __shared__ float act[2][VT][kFixedWidth];
     __shared__ float red[VT * 256];
     const int head = blockIdx.x, v0 = blockIdx.y * VT;
-    uint32_t base = 0;
-    if constexpr (MODE == 1) base = append_base(done);
     constexpr int O0 = NL == 1 ? kBits : D1;            // outputs of layer 0
     constexpr int I1 = D1, O1 = NL == 2 ? kBits : D2;   // layer 1 (NL >= 2)
     constexpr int I2 = D2;                              // layer 2 (NL == 3), 32 outputs
@@ -251,14 +277,21 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
     if constexpr (NL >= 2) fetch_weights<I1, O1>(phi.W[1] + (int64_t)head * I1 * O1, w1);
     if constexpr (NL == 3) fetch_weights<I2, kBits>(phi.W[2] + (int64_t)head * I2 * kBits, w2);
     load_vectors<MODE, kFixedWidth, VT>(act[0], n_heads, head, v0, x, n_vec, n_new);
+    int pos = 0;
+    uint4 piece = make_uint4(0u, 0u, 0u, 0u);
+    if constexpr (MODE == 1) {               // the weights are on their way; the wait in finish_append covers them too
+        const uint32_t base = append_base(done);
+        pos = append_position<VT>(c, v0, n_vec, n_new, n_cap);
+        piece = append_piece<VT>(x, v_new, n_heads, head, v0, n_vec, n_new);
+        finish_append(done, base, fault, c.seq_lens, n_vec / n_new, n_new);
+    }
     __syncthreads();
     gemv_layer<kHeadDim, O0, VT>(w0, phi.bias[0] ? phi.bias[0] + (int64_t)head * O0 : nullptr, act[0], act[1], red, NL == 1);
     if constexpr (NL >= 2)
         gemv_layer<I1, O1, VT>(w1, phi.bias[1] ? phi.bias[1] + (int64_t)head * O1 : nullptr, act[1], act[0], red, NL == 2);
     if constexpr (NL == 3)
         gemv_layer<I2, kBits, VT>(w2, phi.bias[2] ? phi.bias[2] + (int64_t)head * kBits : nullptr, act[0], act[1], red, true);
-    store_codes<MODE, PAGED, kFixedWidth, VT>(act[NL & 1], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, n_cap);
-    if constexpr (MODE == 1) finish_append(done, base, fault, c.seq_lens, n_vec / n_new, n_new);
+    store_codes<MODE, PAGED, kFixedWidth, VT>(act[NL & 1], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, pos, piece);
 }
 
 template <int MODE, bool PAGED, int NL, int D1, int D2>
