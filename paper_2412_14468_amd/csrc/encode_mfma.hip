@@ -15,8 +15,9 @@
 // A[i][k] and B[k][j] sit in lane (i or j) + 32 (k / 8), element k % 8; D[i][j] sits in lane
 // j + 32 g, register r with i = 8 (r / 4) + 4 g + r % 4.  The reduction index may be enumerated in
 // any order as long as A and B agree, which is used twice:
-//   - layer 1: lane (token, g) loads the 128 contiguous bytes g of its key row; step s uses bytes
-//     16 s .. 16 s + 15 of them, i.e. inputs 64 g + 8 s + j;
+//   - layer 1: in step s lane (token, g) loads bytes 32 s + 16 g .. + 15 of its key row, i.e. inputs
+//     16 s + 8 g + j: the two lanes of a token read 32 adjacent bytes, so one load instruction of the wave
+//     touches 32 cache lines rather than 64;
 //   - later layers: the B operand of step s = 2 m + q is made, in registers, from the lane's own
 //     accumulators 8 q .. 8 q + 7 of tile m of the previous layer (units 32 m + 16 q + 8 (j / 4) +
 //     4 g + j % 4) after SiLU and the split: activations never leave the lane.
@@ -80,7 +81,7 @@ __global__ __launch_bounds__(256) void mlp_fragments_kernel(MlpView phi, uint4* 
         for (int e = t0; e < n_elem; e += stride) {
             const int ol = e & 31, kk = (e >> 5) & 15, s = (e >> 9) & 7, m = e >> 12;
             const int g = kk >> 3, j = kk & 7, o = 32 * m + ol;
-            const int k_in = l == 0 ? 64 * g + 8 * s + j
+            const int k_in = l == 0 ? 16 * s + 8 * g + j
                                     : 32 * (s >> 1) + 16 * (s & 1) + 8 * (j >> 2) + 4 * g + (j & 3);
             const float w = W[(int64_t)k_in * dout + o];
             const uint32_t hi = f32_to_bf16(w);
@@ -209,13 +210,13 @@ __global__ __launch_bounds__(mfma_threads(NL)) void encode_bulk_mfma_kernel(KvVi
     for (int i = tid; i < kQuads; i += kMfmaThreads) lds[i] = src[i];
     const float* bias = reinterpret_cast<const float*>(lds + total_frags(NL) * kFragQuads);
 
-    // key rows of a tile: lane (token, g) reads the contiguous 128 bytes g of its row
+    // key rows of a tile: lane (token, g) reads the 16-byte pieces g, g + 2, g + 4, ... of its row
     auto load_rows = [&](int tile, uint4 (&x)[8]) {
         const int t = min(tile * kTileTokens + tl, n_here - 1);          // past the end: repeat the last token
         const int64_t row = row_of<PAGED>(c, b, head, (int)(start + t_blk + t));
-        const uint4* p = reinterpret_cast<const uint4*>(c.k + row * kHeadDim + g * 64);
+        const uint4* p = reinterpret_cast<const uint4*>(c.k + row * kHeadDim) + g;
 #pragma unroll
-        for (int s = 0; s < 8; ++s) x[s] = p[s];
+        for (int s = 0; s < 8; ++s) x[s] = p[2 * s];
     };
     uint4 x[8];
     if (wave < n_tiles) load_rows(wave, x);
