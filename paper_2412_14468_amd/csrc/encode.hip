@@ -124,7 +124,7 @@ __device__ __forceinline__ void store_codes(const float (*a)[WD], int n_heads, i
     const int tid = threadIdx.x;
     const int slot = tid >> 5, j = tid & 31, v = min(slot, VB - 1), vec = v0 + v;
     const bool live = slot < VB && vec < n_vec;
-    const int b = MODE == 0 ? vec : vec / n_new, jn = MODE == 0 ? 0 : vec - b * n_new;
+    const int b = MODE == 0 ? vec : vec / n_new;
     int64_t row = 0;
     if constexpr (MODE == 1) {
         if (live) row = row_of<PAGED>(c, b, head, pos);        // pos: this thread's value of append_position()
