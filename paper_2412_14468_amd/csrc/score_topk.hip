@@ -38,6 +38,44 @@ constexpr int kAllTies = 0x7fffffff;
 constexpr int kBinCopies = 32;        // LDS copies of a histogram bin, one per bank
 constexpr int kChunk = 4 * 4 * kWave; // most tokens a wave handles at once: four 16-byte loads per lane
 
+// Which (sequence, KV head, block inside the sequence) a workgroup takes.  Contiguous cache: a 3-D grid
+// (block, head, sequence), the block index rotated by head and sequence so that the blocks of mixed-length
+// batches spread over the XCDs.  Paged cache: the codes of a page are [head][16 tokens], 64 bytes per head,
+// so a 128-byte line holds the same tokens of two neighbouring heads; fetched by blocks on different XCDs
+// (each with its own L2) every line would cross from memory twice (measured: 2.0 x the code bytes).  There the
+// grid is 1-D and laid out so that the two heads of a pair take workgroup numbers 8 apart: workgroups go to
+// the eight XCDs round-robin, so both land on the same XCD, a few dispatch slots from each other, and the
+// second finds the line in that L2.  Number w = 16 q + 8 p + r (p = head parity, r < 8) takes work item
+// 8 q + r of the list (sequence, block, head pair), pairs fastest.  False: nothing to do (padding).
+template <bool PAGED>
+__device__ __forceinline__ bool block_coords(int nb_cap, int n_kv_heads, int batch, int& b, int& kvh, int& bx)
+{
+    if constexpr (PAGED) {
+        if (n_kv_heads & 1) {                               // no pairs: plain order, heads fastest
+            const int item = blockIdx.x;
+            if (item >= nb_cap * n_kv_heads * batch) return false;
+            kvh = item % n_kv_heads;
+            const int t = item / n_kv_heads;
+            b = t / nb_cap;
+            bx = (t - b * nb_cap + b) % nb_cap;
+            return true;
+        }
+        const int w = blockIdx.x, pairs = n_kv_heads >> 1;
+        const int item = (w >> 4) * 8 + (w & 7);
+        if (item >= nb_cap * pairs * batch) return false;
+        kvh = 2 * (item % pairs) + ((w >> 3) & 1);
+        const int t = item / pairs;
+        b = t / nb_cap;
+        bx = (t - b * nb_cap + b) % nb_cap;                 // rotated by the sequence: block 0, which every sequence has, is not always on the same XCDs
+        return true;
+    } else {
+        b = blockIdx.z;
+        kvh = blockIdx.y;
+        bx = rotated_block(blockIdx.x, kvh + b, gridDim.x);
+        return true;
+    }
+}
+
 // NIT 16-byte loads per lane, coalesced: load `it` of lane L holds tokens base + it * 256 + 4 L .. + 3.
 // Needs base < t_end.  Pieces past t_end repeat the last piece before it instead of being skipped
 // (callers mask by token index), so the loads are unconditional and the compiler can wait for them
@@ -83,14 +121,14 @@ __device__ __forceinline__ void count_chunk(const uint4 (&cw)[4], int base, int 
 template <int G, bool PAGED, int WPB>
 __global__ __launch_bounds__(WPB * kWave) void score_hist_kernel(KvView c, const uint32_t* __restrict__ q_codes,
                                                               int n_q_heads, int n_cap, int unit_tokens,
-                                                              int n_sink, int n_local, int speculate,
+                                                              int n_sink, int n_local, int speculate, int nb_cap, int batch,
                                                               int blocks_pitch, int32_t* __restrict__ blk_cum)
 {
     __shared__ __attribute__((aligned(16))) unsigned hist[G * kBins * kBinCopies];   // [head][score][copy]
     __shared__ int bsum[G * kBins];
     const int tid = threadIdx.x, wave = uniform(tid >> 6), lane = tid & 63;    // wave: scalar, so are the token ranges
-    const int b = blockIdx.z, kvh = blockIdx.y;
-    const int bx = rotated_block(blockIdx.x, kvh + b, gridDim.x);      // block index inside the sequence
+    int b, kvh, bx;                                                     // bx: block index inside the sequence
+    if (!block_coords<PAGED>(nb_cap, c.n_kv_heads, batch, b, kvh, bx)) return;
     const int unit = bx * WPB + wave;
     const int64_t t_begin = (int64_t)unit * unit_tokens;
     // loads complete in issue order: the few small ones go first, so that waiting for them does not
@@ -222,6 +260,7 @@ template <int G, bool PAGED, int NIT, int NCH, int WPB>
 __global__ __launch_bounds__(WPB * kWave) void topk_select_kernel(KvView c, const uint32_t* __restrict__ q_codes,
                                                                const int32_t* __restrict__ k_per_seq, int k_max,
                                                                int n_sink, int n_local, int pitch, int speculate,
+                                                               int nb_cap, int batch,
                                                                int n_q_heads, int n_cap, int blocks_pitch,
                                                                const int32_t* __restrict__ blk_cum,
                                                                int32_t* __restrict__ idx, int32_t* __restrict__ count,
@@ -238,10 +277,9 @@ __global__ __launch_bounds__(WPB * kWave) void topk_select_kernel(KvView c, cons
     __shared__ int thr[G], posb[G], quotab[G];                 // per head: T, first output slot and tie quota of the block
     __shared__ int wcnt[WPB][kPairs], weq[WPB][kPairs];      // per wave: selected / tied tokens, two heads per int
     const int tid = threadIdx.x, wave = uniform(tid >> 6), lane = tid & 63;    // wave: scalar, so are the token ranges
-    const int b = blockIdx.z, kvh = blockIdx.y;
-    const int bx = rotated_block(blockIdx.x, kvh + b, gridDim.x);      // block index inside the sequence
+    int b, kvh, bx;                                            // bx: block index inside the sequence; nb_cap blocks launched per sequence
+    if (!block_coords<PAGED>(nb_cap, c.n_kv_heads, batch, b, kvh, bx)) return;
     const int64_t bh0 = (int64_t)b * n_q_heads + kvh * G;
-    const int nb_cap = gridDim.x;                              // blocks the host launched per sequence
 
     // ---- everything that does not depend on another load is requested first; in a batch of mixed
     // lengths (speculate == 0) the length comes before that, over the scalar path, so that a block
@@ -454,7 +492,7 @@ __global__ __launch_bounds__(WPB * kWave) void topk_select_kernel(KvView c, cons
 
 template <int G, bool PAGED, int NIT, int NCH, int WPB>
 hipError_t select_variant(bool setup_only, const KvView& kv, const TopkCall& a, const TopkScratch& sc, dim3 grid,
-                          hipStream_t stream)
+                          int blocks_per_seq, hipStream_t stream)
 {
     constexpr int lds = NIT > 1 ? WPB * kWave * NIT * (int)sizeof(uint4) : 0;
     if (setup_only)
@@ -462,20 +500,20 @@ hipError_t select_variant(bool setup_only, const KvView& kv, const TopkCall& a, 
                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds);
     topk_select_kernel<G, PAGED, NIT, NCH, WPB><<<grid, dim3(WPB * kWave), lds, stream>>>(
         kv, a.q_codes, a.k_per_seq, a.k_max, a.n_sink, a.n_local, a.k_max + a.n_sink + a.n_local,
-        a.k_per_seq == nullptr, a.n_q_heads,
+        a.k_per_seq == nullptr, blocks_per_seq, a.batch, a.n_q_heads,
         a.max_seq_len, sc.blocks_pitch, sc.blk_cum, a.idx, a.count, a.threshold);
     return hipSuccess;
 }
 
 template <int G, bool PAGED, int WPB>
 hipError_t select_by_unit(bool setup_only, int unit_tokens, const KvView& kv, const TopkCall& a, const TopkScratch& sc,
-                          dim3 grid, hipStream_t stream)
+                          dim3 grid, int blocks_per_seq, hipStream_t stream)
 {
     switch (unit_tokens) {
-    case 256: return select_variant<G, PAGED, 1, 1, WPB>(setup_only, kv, a, sc, grid, stream);
-    case 512: return select_variant<G, PAGED, 2, 1, WPB>(setup_only, kv, a, sc, grid, stream);
-    case 1024: return select_variant<G, PAGED, 4, 1, WPB>(setup_only, kv, a, sc, grid, stream);
-    case 2048: return select_variant<G, PAGED, 4, 2, WPB>(setup_only, kv, a, sc, grid, stream);
+    case 256: return select_variant<G, PAGED, 1, 1, WPB>(setup_only, kv, a, sc, grid, blocks_per_seq, stream);
+    case 512: return select_variant<G, PAGED, 2, 1, WPB>(setup_only, kv, a, sc, grid, blocks_per_seq, stream);
+    case 1024: return select_variant<G, PAGED, 4, 1, WPB>(setup_only, kv, a, sc, grid, blocks_per_seq, stream);
+    case 2048: return select_variant<G, PAGED, 4, 2, WPB>(setup_only, kv, a, sc, grid, blocks_per_seq, stream);
     default: return hipErrorInvalidValue;
     }
 }
@@ -486,18 +524,27 @@ hipError_t launch_gpw(bool setup_only, const KvView& kv, const TopkCall& a, int 
 {
     if (setup_only) {
         for (int unit = 256; unit <= 2048; unit *= 2)
-            if (hipError_t e = select_by_unit<G, PAGED, WPB>(true, unit, kv, a, sc, dim3(1), stream); e != hipSuccess) return e;
+            if (hipError_t e = select_by_unit<G, PAGED, WPB>(true, unit, kv, a, sc, dim3(1), 1, stream); e != hipSuccess) return e;
         return hipSuccess;
     }
     const int64_t block_tokens = (int64_t)WPB * unit_tokens;
     int n_blocks = (int)((a.max_seq_len + block_tokens - 1) / block_tokens);
     if (n_blocks < 1) n_blocks = 1;               // block 0 of every group still reports count = 0
-    const dim3 grid(n_blocks, kv.n_kv_heads, a.batch), block(WPB * kWave);
+    // contiguous: (block, head, sequence); paged: 1-D, head pairs eight workgroup numbers apart (block_coords)
+    dim3 grid(n_blocks, kv.n_kv_heads, a.batch);
+    if constexpr (PAGED) {
+        const int64_t n_kv = kv.n_kv_heads;
+        const int64_t items = (n_kv & 1) ? (int64_t)n_blocks * n_kv * a.batch : (int64_t)n_blocks * (n_kv / 2) * a.batch;
+        const int64_t groups = (n_kv & 1) ? items : (items + 7) / 8 * 16;
+        if (groups > 0x7fffffff) return hipErrorInvalidValue;
+        grid = dim3((unsigned)groups);
+    }
+    const dim3 block(WPB * kWave);
     // a k per sequence means lengths differ: blocks then wait for their sequence's length before any other load
     score_hist_kernel<G, PAGED, WPB><<<grid, block, 0, stream>>>(kv, a.q_codes, a.n_q_heads, a.max_seq_len, unit_tokens,
-                                                             a.n_sink, a.n_local, a.k_per_seq == nullptr, sc.blocks_pitch,
-                                                             sc.blk_cum);
-    if (hipError_t e = select_by_unit<G, PAGED, WPB>(false, unit_tokens, kv, a, sc, grid, stream); e != hipSuccess) return e;
+                                                             a.n_sink, a.n_local, a.k_per_seq == nullptr, n_blocks, a.batch,
+                                                             sc.blocks_pitch, sc.blk_cum);
+    if (hipError_t e = select_by_unit<G, PAGED, WPB>(false, unit_tokens, kv, a, sc, grid, n_blocks, stream); e != hipSuccess) return e;
     return hipGetLastError();
 }
 

@@ -70,3 +70,16 @@ def test_random_paged_whole_steps(seed):
     print(f"paged case {seed}: batch={batch} lengths in [{lo}, {hi}] heads={heads} k=N/{cfg.k_divisor}", flush=True)
     L = W.make_layer(cfg, seed=500 + seed)
     run_whole_step(L)
+
+
+@pytest.mark.parametrize("heads", [(6, 3), (5, 5), (12, 6), (4, 4)])
+def test_paged_head_counts_odd_and_even(heads):
+    """Paged SCORE + TOPK numbers its workgroups so that neighbouring KV heads share a cache line's fetch, with
+    a plain order for an odd head count: whole steps at both kinds, more items than one group of eight."""
+    import workloads as W
+    import gpu_util
+    import test_gpu_parity
+    test_gpu_parity.gu = gpu_util
+    cfg = W.scaled(W.c4(batch=5, lo=40, hi=9000), planted=4, n_q_heads=heads[0], n_kv_heads=heads[1], k_divisor=16)
+    L = W.make_layer(cfg, seed=900 + heads[0])
+    test_gpu_parity.run_whole_step(L)
