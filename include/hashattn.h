@@ -115,6 +115,12 @@ int64_t hashattn_scratch_bytes(const hashattn_ctx* ctx);
  * after `value` of its blocks would (>= 0; 0 is the normal state).  Not needed
  * by any caller of the path. */
 hashattn_status hashattn_selftest_set_append_counter(hashattn_ctx* ctx, int32_t value, void* stream);
+/* For tests: SCORE + TOPK has a one-launch form for short contexts and few
+ * (sequence, head) pairs and a two-launch form for everything else, with
+ * identical results.  path 0 (the default) lets every call choose, 1 always
+ * takes two launches, 2 takes one launch whenever the context length allows
+ * it (at most 32768 tokens, 32-bit signatures).  Host state only. */
+hashattn_status hashattn_selftest_set_topk_path(hashattn_ctx* ctx, int32_t path);
 
 /* Key signatures phi_int,kv(k), computed when a token enters the KV cache and
  * stored beside it (section 4.1, "Implementation" paragraph; phi_kv reads the
@@ -181,6 +187,27 @@ hashattn_status hashattn_score_topk_window(hashattn_ctx* ctx, const uint32_t* q_
                                            const hashattn_kv* cache, int32_t batch,
                                            const int32_t* k_per_seq, int32_t k_max,
                                            int32_t n_sink, int32_t n_local,
+                                           int32_t* idx, int32_t* count, uint8_t* threshold,
+                                           void* stream);
+
+/* ENCODE-Q, SCORE and TOPK in one call (section 4: eq. 2 for the query, eq. 1
+ * for the scores, the standard top-k over them): q_codes[b][h] is the code of
+ * q[b][h] under phi_q as hashattn_encode_query computes it, and idx, count
+ * and threshold are what hashattn_score_topk_window gives for those codes.
+ * With at most 512 (sequence, query head) pairs, max_seq_len <= 32768, 32-bit
+ * signatures and a mapping of 2 or 3 layers of width 128 this is one kernel
+ * launch instead of three, which is most of the time of a decode step at
+ * batch 1 and a short context; any other shape runs the two calls one after
+ * the other.  In the one-launch form the partial sums of a layer are added in
+ * another order than in hashattn_encode_query, so a bit of q_codes whose
+ * activation is within float rounding of zero can differ between the two.
+ *   q        dev bf16 [batch][n_q_heads][128] (input)
+ *   q_codes  dev uint32 [batch][n_q_heads] (output)
+ * Everything else as in hashattn_score_topk_window. */
+hashattn_status hashattn_encode_score_topk(hashattn_ctx* ctx, const hashattn_mlp* phi_q, const void* q,
+                                           const hashattn_kv* cache, int32_t batch,
+                                           const int32_t* k_per_seq, int32_t k_max,
+                                           int32_t n_sink, int32_t n_local, uint32_t* q_codes,
                                            int32_t* idx, int32_t* count, uint8_t* threshold,
                                            void* stream);
 

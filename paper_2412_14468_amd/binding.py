@@ -68,6 +68,8 @@ def load() -> C.CDLL:
     L.hashattn_scratch_bytes.argtypes = [vp]
     L.hashattn_selftest_set_append_counter.restype = i32
     L.hashattn_selftest_set_append_counter.argtypes = [vp, i32, vp]
+    L.hashattn_selftest_set_topk_path.restype = i32
+    L.hashattn_selftest_set_topk_path.argtypes = [vp, i32]
     L.hashattn_encode_keys.restype = i32
     L.hashattn_encode_keys.argtypes = [vp, C.POINTER(MlpStruct), vp, vp, i32, i64, C.POINTER(KvStruct), vp]
     L.hashattn_encode_query.restype = i32
@@ -76,6 +78,8 @@ def load() -> C.CDLL:
     L.hashattn_score_topk.argtypes = [vp, vp, C.POINTER(KvStruct), i32, vp, i32, vp, vp, vp, vp]
     L.hashattn_score_topk_window.restype = i32
     L.hashattn_score_topk_window.argtypes = [vp, vp, C.POINTER(KvStruct), i32, vp, i32, i32, i32, vp, vp, vp, vp]
+    L.hashattn_encode_score_topk.restype = i32
+    L.hashattn_encode_score_topk.argtypes = [vp, C.POINTER(MlpStruct), vp, C.POINTER(KvStruct), i32, vp, i32, i32, i32, vp, vp, vp, vp, vp]
     L.hashattn_gather_attend.restype = i32
     L.hashattn_gather_attend.argtypes = [vp, vp, C.POINTER(KvStruct), vp, vp, i32, i32, C.c_float, vp, vp]
     L.hashattn_gather_attend_noalloc.restype = i32
@@ -192,6 +196,9 @@ class Context:
     def scratch_bytes(self) -> int:
         return int(load().hashattn_scratch_bytes(self.h))
 
+    def hashattn_selftest_set_topk_path(self, path: int) -> None:
+        self._check(load().hashattn_selftest_set_topk_path(self.h, int(path)))
+
     def hashattn_selftest_set_append_counter(self, value: int, stream=None) -> None:
         self._check(load().hashattn_selftest_set_append_counter(self.h, int(value), _stream(stream)))
 
@@ -214,6 +221,12 @@ class Context:
                                    n_local: int, idx, count, threshold=None, stream=None) -> None:
         self._check(load().hashattn_score_topk_window(self.h, _ptr(q_codes), C.byref(cache.c), batch,
                                                       _ptr(k_per_seq), k_max, n_sink, n_local, _ptr(idx),
+                                                      _ptr(count), _ptr(threshold), _stream(stream)))
+
+    def hashattn_encode_score_topk(self, phi_q: Mlp, q, cache: KvCache, batch: int, k_per_seq, k_max: int, n_sink: int,
+                                   n_local: int, q_codes, idx, count, threshold=None, stream=None) -> None:
+        self._check(load().hashattn_encode_score_topk(self.h, C.byref(phi_q.c), _ptr(q), C.byref(cache.c), batch,
+                                                      _ptr(k_per_seq), k_max, n_sink, n_local, _ptr(q_codes), _ptr(idx),
                                                       _ptr(count), _ptr(threshold), _stream(stream)))
 
     def hashattn_gather_attend(self, q, cache: KvCache, idx, count, batch: int, k_max: int, scale: float, out,

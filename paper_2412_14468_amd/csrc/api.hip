@@ -17,6 +17,7 @@ struct hashattn_ctx {
     // TOPK scratch
     int32_t* blk_cum;
     int32_t blocks_pitch;
+    int32_t topk_path;            // 0: chosen per call; 1: always two launches; 2: one launch whenever the shape allows
     uint4* frags;                 // bf16 weight fragments of the matrix-core key encoder, per KV head
     uint32_t* append_done;        // two-word block counter of the decode-time append kernel (see finish_append)
     int32_t* append_fault_host;   // pinned host word an append launch raises when it finds that counter inconsistent
@@ -165,6 +166,16 @@ int pick_unit_tokens(const hashattn_ctx* ctx, int batch, int max_seq_len, bool m
     return unit;
 }
 
+// SCORE + TOPK in one launch (a block per sequence and query head) or in two (blocks per KV head and piece of
+// the sequence).  One launch wins while its blocks, each as long as the sequence, all fit on the chip's 256
+// compute units at once, two to a unit (measured at 2K to 32K tokens: ahead up to 512 blocks, behind at 1024).
+bool one_launch_topk(const hashattn_ctx* ctx, int batch, int max_seq_len)
+{
+    if (ctx->cfg.bits != ha::kBits || max_seq_len > ha::score_topk_one_block_limit() || ctx->topk_path == 1) return false;
+    if (ctx->topk_path == 2) return true;
+    return (int64_t)batch * ctx->cfg.n_q_heads <= 512;
+}
+
 // Split shape for the attention kernels: `total` tokens per (sequence, head), `lanes` independent
 // (sequence, head) pairs that share the launch.  About a thousand blocks fill the chip; pieces of
 // at most `max_chunk` tokens keep a batch of mixed lengths balanced (the grid is sized by the
@@ -308,6 +319,14 @@ hashattn_status hashattn_selftest_set_append_counter(hashattn_ctx* ctx, int32_t 
     return e == hipSuccess ? HASHATTN_OK : hip_fail(ctx, e, "selftest_set_append_counter");
 }
 
+hashattn_status hashattn_selftest_set_topk_path(hashattn_ctx* ctx, int32_t path)
+{
+    if (!ctx) return HASHATTN_INVALID_ARG;
+    if (path < 0 || path > 2) return fail(ctx, HASHATTN_INVALID_ARG, "selftest_set_topk_path: path %d is not 0, 1 or 2", path);
+    ctx->topk_path = path;
+    return HASHATTN_OK;
+}
+
 hashattn_status hashattn_encode_keys(hashattn_ctx* ctx, const hashattn_mlp* phi_kv, const void* k_new,
                                      const void* v_new, int32_t batch, int64_t n_new, hashattn_kv* cache,
                                      void* stream)
@@ -375,6 +394,11 @@ hashattn_status hashattn_score_topk_window(hashattn_ctx* ctx, const uint32_t* q_
     const int unit = pick_unit_tokens(ctx, batch, cache->max_seq_len, k_per_seq != nullptr, &wpb);
     const ha::TopkCall call{q_codes, k_per_seq, k_max, n_sink, n_local, batch, ctx->cfg.n_q_heads, cache->max_seq_len,
                             wpb, idx, count, threshold};
+    if (one_launch_topk(ctx, batch, cache->max_seq_len)) {
+        const hipError_t e1 = ha::launch_score_topk_one_block(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group, call,
+                                                              nullptr, nullptr, static_cast<hipStream_t>(stream));
+        return e1 == hipSuccess ? HASHATTN_OK : hip_fail(ctx, e1, "score_topk");
+    }
     const hipError_t e = ctx->cfg.bits == ha::kBits
         ? ha::launch_score_topk(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group, call, unit, sc,
                                 static_cast<hipStream_t>(stream))
@@ -388,6 +412,40 @@ hashattn_status hashattn_score_topk(hashattn_ctx* ctx, const uint32_t* q_codes, 
                                     int32_t* count, uint8_t* threshold, void* stream)
 {
     return hashattn_score_topk_window(ctx, q_codes, cache, batch, k_per_seq, k_max, 0, 0, idx, count, threshold, stream);
+}
+
+hashattn_status hashattn_encode_score_topk(hashattn_ctx* ctx, const hashattn_mlp* phi_q, const void* q,
+                                           const hashattn_kv* cache, int32_t batch, const int32_t* k_per_seq,
+                                           int32_t k_max, int32_t n_sink, int32_t n_local, uint32_t* q_codes,
+                                           int32_t* idx, int32_t* count, uint8_t* threshold, void* stream)
+{
+    if (!ctx) return HASHATTN_INVALID_ARG;
+    // one launch when the shape allows it and the mapping is one the kernel has; every argument is then
+    // checked here as the two calls would check it
+    const bool one = phi_q && cache && one_launch_topk(ctx, batch, cache->max_seq_len) && phi_q->n_layers >= 1 &&
+                     phi_q->n_layers <= 4 && ha::one_block_can_encode(view_of(phi_q));
+    if (!one) {
+        if (hashattn_status s = hashattn_encode_query(ctx, phi_q, q, batch, q_codes, stream)) return s;
+        return hashattn_score_topk_window(ctx, q_codes, cache, batch, k_per_seq, k_max, n_sink, n_local, idx, count,
+                                          threshold, stream);
+    }
+    if (hashattn_status s = check_append_state(ctx, "encode_score_topk")) return s;
+    if (hashattn_status s = check_mlp(ctx, phi_q, ctx->cfg.n_q_heads, "encode_score_topk")) return s;
+    if (hashattn_status s = check_cache(ctx, cache, batch, true, "encode_score_topk")) return s;
+    if (!q || !q_codes || !idx || !count) return fail(ctx, HASHATTN_INVALID_ARG, "encode_score_topk: q, q_codes, idx or count is NULL");
+    if (!aligned(q, 16) || !aligned(q_codes, 4) || !aligned(idx, 4) || !aligned(count, 4) || (k_per_seq && !aligned(k_per_seq, 4)))
+        return fail(ctx, HASHATTN_INVALID_ARG, "encode_score_topk: q needs 16-byte alignment, the integer arrays 4-byte");
+    if (k_max < 1) return fail(ctx, HASHATTN_INVALID_ARG, "encode_score_topk: k_max %d < 1", k_max);
+    if (n_sink < 0 || n_local < 0) return fail(ctx, HASHATTN_INVALID_ARG, "encode_score_topk: n_sink %d or n_local %d is negative", n_sink, n_local);
+    if ((int64_t)k_max + n_sink + n_local > ctx->cfg.max_k)
+        return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "encode_score_topk: k_max + n_sink + n_local = %lld exceeds max_k %lld",
+                    (long long)k_max + n_sink + n_local, (long long)ctx->cfg.max_k);
+    const ha::TopkCall call{q_codes, k_per_seq, k_max, n_sink, n_local, batch, ctx->cfg.n_q_heads, cache->max_seq_len,
+                            0, idx, count, threshold};
+    const ha::MlpView phi = view_of(phi_q);
+    const hipError_t e = ha::launch_score_topk_one_block(view_of(ctx, cache), ctx->cfg.page_size != 0, ctx->group, call, &phi,
+                                                         static_cast<const uint16_t*>(q), static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? HASHATTN_OK : hip_fail(ctx, e, "encode_score_topk");
 }
 
 hashattn_status hashattn_gather_attend(hashattn_ctx* ctx, const void* q, const hashattn_kv* cache, const int32_t* idx,

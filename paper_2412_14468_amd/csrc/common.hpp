@@ -57,6 +57,7 @@ __device__ __forceinline__ int64_t row_in_page(const KvView& c, int b, int h, in
 
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return __uint_as_float(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
+__device__ __forceinline__ float silu(float z) { return z / (1.f + expf(-z)); }
 
 // fp32 -> bf16 bits, round to nearest even (inputs are finite here).
 __device__ __forceinline__ uint32_t f32_to_bf16(float f)

@@ -23,7 +23,6 @@ constexpr int kFixedWidth = 256;      // activation pitch of the kernels with co
 constexpr int kVecPerBlock = 8;
 constexpr int kTile = 64;
 
-__device__ __forceinline__ float silu(float z) { return z / (1.f + expf(-z)); }
 
 // ---------------------------------------------------------------- encode_vec
 // act: [2][kVecPerBlock][kMaxWidth] floats; r: kVecPerBlock * 256 floats of partial sums, indexed

@@ -66,6 +66,13 @@ struct TopkCall {
 
 hipError_t launch_score_topk(const KvView& kv, bool paged, int group, const TopkCall& call, int unit_tokens,
                              const TopkScratch& sc, hipStream_t stream);
+// SCORE + TOPK in one launch, one block per (sequence, query head), for max_seq_len up to the limit.  With a
+// query mapping `phi` that one_block_can_encode accepts and the query vectors `q`, the blocks compute the
+// query codes first and write them to call.q_codes; with phi = NULL they read call.q_codes.
+int score_topk_one_block_limit();
+bool one_block_can_encode(const MlpView& phi);
+hipError_t launch_score_topk_one_block(const KvView& kv, bool paged, int group, const TopkCall& call, const MlpView* phi,
+                                       const uint16_t* q, hipStream_t stream);
 
 // Signatures of 32 * words bits (words = 2, 4, 8, 16): codes and q_codes carry a trailing axis of
 // `words`, blk_cum rows have 32 * words + 2 ints, unit_tokens is at most 1024.

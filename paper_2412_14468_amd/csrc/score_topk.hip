@@ -584,13 +584,330 @@ hipError_t dispatch_group(bool setup_only, const KvView& kv, bool paged, int gro
     }
 }
 
+
+// ---------------------------------------------------------------------------------------------------
+// One launch for short contexts.  With few (sequence, head) pairs and a context of a few ten thousand
+// tokens the two kernels above are launch and round-trip latency: tables written, a kernel boundary, the
+// tables and the codes fetched again.  Here one block of 16 waves owns a whole (sequence, query head): a wave
+// keeps its unit's codes in registers (NCH chunks of 1024 tokens), counts the scores into a histogram of its
+// own in LDS, and leaves its 33 bin counts in a table of the block; after the one block barrier every wave
+// reads the table, works out T, the tie quota and its own first output slot (waves are in token order), and
+// emits its ids from the registers it still holds.  The KV head's codes are read by each of its query
+// heads' blocks (from L2 after the first), which costs less than a second launch.
+// NL > 0: the block also maps its query vector to the code first (eq. 2; NL layers 128 -> 128 (-> 128) -> 32
+// with SiLU between them), with the codes of the keys already on their way, and leaves the code in q_codes:
+// ENCODE-Q, SCORE and TOPK in one launch.  The 1024 threads split a layer's inputs eight ways (32 ways for
+// the last layer) and add the parts in a fixed order, so the code does not depend on timing; the order is
+// not that of the stand-alone query encoder, so a bit whose activation is within rounding of zero may differ
+// from it.
+constexpr int kOneWaves = 16;
+constexpr int kOneLdsPerWave = kBins * kBinCopies * (int)sizeof(unsigned);   // histogram, later the staging area (4096 B) of to_lane_runs
+static_assert(kOneLdsPerWave >= 4 * kWave * (int)sizeof(uint4), "the staging area of a wave lies inside its histogram");
+
+template <bool PAGED, int NCH, int NL>
+__global__ __launch_bounds__(kOneWaves * kWave) void score_topk_one_block_kernel(
+    KvView c, MlpView phi, const uint16_t* __restrict__ q, uint32_t* __restrict__ q_codes,
+    const int32_t* __restrict__ k_per_seq, int k_max, int n_sink,
+    int n_local, int pitch, int n_q_heads, int group, int n_cap, int32_t* __restrict__ idx,
+    int32_t* __restrict__ count, uint8_t* __restrict__ threshold)
+{
+    constexpr int kTpl = 16, kChunkTokens = kTpl * kWave, kUnitTokens = kChunkTokens * NCH;
+    extern __shared__ uint4 lds_all[];                          // kOneLdsPerWave bytes per wave
+    __shared__ int wbins[kOneWaves][kCumRow];                   // per wave: #{score == s}, slot 33 = 0
+    const int tid = threadIdx.x, wave = uniform(tid >> 6), lane = tid & 63;
+    const int h = blockIdx.x, b = blockIdx.y, kvh = h / group;
+    const int64_t bh = (int64_t)b * n_q_heads + h;
+    unsigned* whist = reinterpret_cast<unsigned*>(reinterpret_cast<char*>(lds_all) + wave * kOneLdsPerWave);
+
+    // ---- requests in the order their answers are needed (loads complete in issue order): query vector and
+    // mapping weights, lengths, then the codes
+    constexpr int kHid = 128;                                   // hidden width and input width of the mapping
+    __shared__ float mlp_in[2][kHid];
+    __shared__ float mlp_red[kOneWaves * kWave];
+    __shared__ uint32_t q_code_of_block;
+    const int mj = tid & (kHid - 1), mp = tid >> 7;             // hidden layers: output mj, inputs 16 mp .. 16 mp + 15
+    const int lj = tid & (kBits - 1), lp = tid >> 5;            // last layer: output lj, inputs 4 lp .. 4 lp + 3
+    float w_hid[NL > 0 ? NL - 1 : 1][16], w_last[4];
+    int qraw = 0;
+    if constexpr (NL == 0) {
+        qraw = (int)q_codes[bh];
+    } else {
+        if (tid < kHid / 2) {
+            const uint32_t two = reinterpret_cast<const uint32_t*>(q)[bh * (kHid / 2) + tid];
+            mlp_in[0][2 * tid] = bf16_lo(two);
+            mlp_in[0][2 * tid + 1] = bf16_hi(two);
+        }
+#pragma unroll
+        for (int l = 0; l < NL - 1; ++l) {
+            const float* W = phi.W[l] + (int64_t)h * kHid * kHid;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) w_hid[l][i] = W[(mp * 16 + i) * kHid + mj];
+        }
+        const float* W = phi.W[NL - 1] + (int64_t)h * kHid * kBits;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) w_last[i] = W[(lp * 4 + i) * kBits + lj];
+    }
+    const int n_raw = c.seq_lens[b];
+    const int k_raw = k_per_seq ? k_per_seq[b] : k_max;
+    const int t_begin = wave * kUnitTokens;
+    uint4 cw[NCH][4];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch)
+#pragma unroll
+        for (int it = 0; it < 4; ++it) cw[ch][it] = make_uint4(0u, 0u, 0u, 0u);
+    constexpr bool early = !PAGED;         // contiguous cache: rows up to n_cap exist, no need to wait for the length
+    if (early) {
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch)
+            if (t_begin + ch * kChunkTokens < n_cap)
+                load_chunk<PAGED, 4>(c, b, kvh, t_begin + ch * kChunkTokens, min(n_cap, t_begin + kUnitTokens), lane, cw[ch]);
+    }
+    for (int i = lane; i < kBins * kBinCopies; i += kWave) whist[i] = 0u;
+    const int n = min(n_raw, n_cap);
+    const int lo = min(n_sink, n), hi = max(lo, n - n_local);
+    const int k = max(0, min(k_raw, min(k_max, hi - lo)));
+    const bool nothing = k == 0 && lo == 0 && hi == n;
+    const bool active = t_begin < n && !nothing;
+    const int t_end = min(n, t_begin + kUnitTokens);
+    if (!early && active) {
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch)
+            if (t_begin + ch * kChunkTokens < t_end)
+                load_chunk<PAGED, 4>(c, b, kvh, t_begin + ch * kChunkTokens, t_end, lane, cw[ch]);
+    }
+    if constexpr (NL > 0) {
+        // ---- the query's code (eq. 2)
+        __syncthreads();
+#pragma unroll
+        for (int l = 0; l < NL - 1; ++l) {
+            const float* in = mlp_in[l & 1];
+            float acc = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc = fmaf(in[mp * 16 + i], w_hid[l][i], acc);
+            mlp_red[mp * kHid + mj] = acc;
+            __syncthreads();
+            if (tid < kHid) {
+                float z = 0.f;
+#pragma unroll
+                for (int pp = 0; pp < kOneWaves * kWave / kHid; ++pp) z += mlp_red[pp * kHid + tid];
+                if (phi.bias[l]) z += phi.bias[l][(int64_t)h * kHid + tid];
+                mlp_in[(l + 1) & 1][tid] = silu(z);
+            }
+            __syncthreads();
+        }
+        const float* in = mlp_in[(NL - 1) & 1];
+        float acc = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc = fmaf(in[lp * 4 + i], w_last[i], acc);
+        mlp_red[lp * kBits + lj] = acc;
+        __syncthreads();
+        if (wave == 0) {
+            float z = 0.f;
+            if (lane < kBits) {
+#pragma unroll
+                for (int pp = 0; pp < kOneWaves * kWave / kBits; ++pp) z += mlp_red[pp * kBits + lane];
+                if (phi.bias[NL - 1]) z += phi.bias[NL - 1][(int64_t)h * kBits + lane];
+            }
+            const uint32_t code = (uint32_t)__ballot(lane < kBits && z > 0.f);     // output unit j is bit j
+            if (lane == 0) {
+                q_code_of_block = code;
+                q_codes[bh] = code;
+            }
+        }
+        __syncthreads();
+        qraw = (int)q_code_of_block;
+    }
+    const uint32_t qc = (uint32_t)uniform(qraw);
+    const uint32_t nqc[1] = {(uint32_t)uniform(~qraw)};
+    wave_lds_order();
+
+    // ---- the wave's histogram, then its 33 bin counts
+    if (active) {
+        unsigned* mine = whist + (lane & (kBinCopies - 1));
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+            const int base = t_begin + ch * kChunkTokens;
+            if (base < t_end) {
+                if (base >= lo && base + kChunkTokens <= min(t_end, hi)) count_chunk<1, false>(cw[ch], base, lo, hi, lane, nqc, mine);
+                else count_chunk<1, true>(cw[ch], base, lo, min(t_end, hi), lane, nqc, mine);
+            }
+        }
+    }
+    wave_lds_order();
+    for (int row0 = 0; row0 < kCumRow; row0 += 8) {             // eight lanes add the 32 copies of a bin
+        const int row = row0 + (lane >> 3);
+        int s = 0;
+        if (row < kBins) {
+            const uint4 x = *reinterpret_cast<const uint4*>(whist + row * kBinCopies + (lane & 7) * 4);
+            s = (int)((x.x + x.y) + (x.z + x.w));
+        }
+        s += dpp_i<0xB1>(s);    // quad_perm:[1,0,3,2]
+        s += dpp_i<0x4E>(s);    // quad_perm:[2,3,0,1]
+        s += __shfl_xor(s, 4, kWave);
+        if ((lane & 7) == 0 && row < kCumRow) wbins[wave][row] = s;
+    }
+    __syncthreads();
+
+    // ---- every wave: counts over the sequence, before itself, its own; T, quota, first slot
+    int tot = 0, bef = 0, own = 0;
+    if (lane < kCumRow) {
+#pragma unroll
+        for (int w = 0; w < kOneWaves; ++w) {
+            const int v = wbins[w][lane];
+            tot += v;
+            if (w < wave) bef += v;
+            if (w == wave) own = v;
+        }
+    }
+    const int tot_incl = wave_incl_scan_i32(tot), bef_incl = wave_incl_scan_i32(bef);
+    const int cum = __builtin_amdgcn_readlane(tot_incl, 63) - tot_incl + tot;        // #{score >= lane} over the sequence
+    const int cum_bef = __builtin_amdgcn_readlane(bef_incl, 63) - bef_incl + bef;    // the same over the waves before this one
+    int T = kBins, r = 0, gt = 0, eq_before = 0, own_eq = 0;
+    if (k > 0) {
+        const uint64_t ge_k = __ballot(lane < kBins && cum >= k);
+        T = 63 - __clzll((long long)(ge_k | 1ull));
+        r = k - __shfl(cum, T + 1, kWave);                      // slot 33 holds 0
+        gt = __shfl(cum_bef, T + 1, kWave);
+        eq_before = __shfl(bef, T, kWave);
+        own_eq = __shfl(own, T, kWave);
+    }
+    T = uniform(T);
+    const int left = uniform(r - eq_before);                    // tie quota still open at this wave
+    const int quota = left >= own_eq ? kAllTies : max(left, 0);
+    const int lim = quota == kAllTies ? kBits - T : kBits - T - 1;   // bound on the Hamming distance 32 - score
+    const bool partial = quota != kAllTies && quota != 0;
+    const int ws = min(n, t_begin);                             // always-kept tokens before this wave
+    int start = uniform(gt + min(eq_before, r) + min(lo, ws) + max(0, ws - hi));
+    if (tid == 0) {
+        count[bh] = lo + k + (n - hi);
+        if (threshold) threshold[bh] = (uint8_t)(k > 0 ? T : 0);
+    }
+    if (!active) return;
+
+    // ---- masks from the codes still in registers, ties ranked in token order, ids
+    uint4* stage = reinterpret_cast<uint4*>(whist);
+    unsigned sel[NCH], tie[NCH];
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+        sel[ch] = tie[ch] = 0u;
+        const int cbase = t_begin + ch * kChunkTokens;
+        if (cbase < t_end) {
+            uint32_t w[kTpl];
+            to_lane_runs<4>(cw[ch], stage, lane, w);
+            const int first = cbase + lane * kTpl;
+            auto below = [&](int t) { return (1u << max(0, min(t - first, kTpl))) - 1u; };
+            const unsigned valid = below(t_end);
+            const unsigned scored = below(hi) & ~below(lo) & valid;
+            sel[ch] = (within_mask<kTpl>(w, qc, lim) & scored) | (valid & ~scored);
+            if (partial) tie[ch] = equal_mask<kTpl>(w, qc, lim + 1) & scored;
+        }
+    }
+    if (partial) {
+        int seen = 0;
+#pragma unroll
+        for (int ch = 0; ch < NCH; ++ch) {
+            const int mine = __popc(tie[ch]);
+            const int incl = wave_incl_scan_i32(mine);
+            const int take = max(0, min(mine, quota - seen - (incl - mine)));
+            sel[ch] |= lowest_bits(tie[ch], take);
+            seen += __builtin_amdgcn_readlane(incl, 63);
+        }
+    }
+    int32_t* out = idx + bh * pitch;
+#pragma unroll
+    for (int ch = 0; ch < NCH; ++ch) {
+        const int c0 = __popc(sel[ch]);
+        const int incl = wave_incl_scan_i32(c0);
+        emit_ids(sel[ch], start + incl - c0, t_begin + ch * kChunkTokens + lane * kTpl, pitch, out);
+        start += __builtin_amdgcn_readlane(incl, 63);
+    }
+}
+
+// What the one-launch kernel is to encode with: nothing (q_codes are given), or a query mapping of 2 or 3 layers.
+struct OneBlockEncode {
+    int n_layers = 0;
+    MlpView phi{};
+    const uint16_t* q = nullptr;
+};
+
+template <bool PAGED, int NCH, int NL>
+hipError_t one_block_variant(bool setup_only, const KvView& kv, int group, const TopkCall& a, const OneBlockEncode& enc,
+                             hipStream_t stream)
+{
+    constexpr int lds = kOneWaves * kOneLdsPerWave;
+    if (setup_only)
+        return hipFuncSetAttribute(reinterpret_cast<const void*>(&score_topk_one_block_kernel<PAGED, NCH, NL>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds);
+    score_topk_one_block_kernel<PAGED, NCH, NL><<<dim3(a.n_q_heads, a.batch), dim3(kOneWaves * kWave), lds, stream>>>(
+        kv, enc.phi, enc.q, const_cast<uint32_t*>(a.q_codes), a.k_per_seq, a.k_max, a.n_sink, a.n_local,
+        a.k_max + a.n_sink + a.n_local, a.n_q_heads, group, a.max_seq_len, a.idx, a.count, a.threshold);
+    return hipGetLastError();
+}
+
+template <bool PAGED, int NCH>
+hipError_t one_block_by_layers(bool setup_only, const KvView& kv, int group, const TopkCall& a, const OneBlockEncode& enc,
+                               hipStream_t stream)
+{
+    if (setup_only) {
+        if (hipError_t e = one_block_variant<PAGED, NCH, 0>(true, kv, group, a, enc, stream); e != hipSuccess) return e;
+        if (hipError_t e = one_block_variant<PAGED, NCH, 2>(true, kv, group, a, enc, stream); e != hipSuccess) return e;
+        return one_block_variant<PAGED, NCH, 3>(true, kv, group, a, enc, stream);
+    }
+    switch (enc.n_layers) {
+    case 0: return one_block_variant<PAGED, NCH, 0>(false, kv, group, a, enc, stream);
+    case 2: return one_block_variant<PAGED, NCH, 2>(false, kv, group, a, enc, stream);
+    case 3: return one_block_variant<PAGED, NCH, 3>(false, kv, group, a, enc, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+template <bool PAGED>
+hipError_t one_block_by_length(bool setup_only, const KvView& kv, int group, const TopkCall& a, const OneBlockEncode& enc,
+                               hipStream_t stream)
+{
+    if (setup_only) {
+        if (hipError_t e = one_block_by_layers<PAGED, 1>(true, kv, group, a, enc, stream); e != hipSuccess) return e;
+        return one_block_by_layers<PAGED, 2>(true, kv, group, a, enc, stream);
+    }
+    return a.max_seq_len <= kOneWaves * 1024 ? one_block_by_layers<PAGED, 1>(false, kv, group, a, enc, stream)
+                                             : one_block_by_layers<PAGED, 2>(false, kv, group, a, enc, stream);
+}
+
 }  // namespace
 
 // Raises the dynamic LDS limit of the select kernels of this group size (their staging area reaches
 // 64 KiB); called once when a context is created, never on the launch path.
 hipError_t setup_score_topk(int group)
 {
+    if (hipError_t e = one_block_by_length<false>(true, KvView{}, group, TopkCall{}, OneBlockEncode{}, nullptr); e != hipSuccess) return e;
+    if (hipError_t e = one_block_by_length<true>(true, KvView{}, group, TopkCall{}, OneBlockEncode{}, nullptr); e != hipSuccess) return e;
     return dispatch_group(true, KvView{}, false, group, TopkCall{}, 0, TopkScratch{}, nullptr);
+}
+
+// Most tokens per sequence the one-launch path takes: 16 waves with two chunks of 1024 tokens each.
+int score_topk_one_block_limit() { return kOneWaves * 2 * 1024; }
+
+bool one_block_can_encode(const MlpView& phi)
+{
+    if (phi.n_layers != 2 && phi.n_layers != 3) return false;
+    for (int l = 0; l < phi.n_layers; ++l)
+        if (phi.dims[l] != 128) return false;
+    return phi.dims[phi.n_layers] == kBits;
+}
+
+hipError_t launch_score_topk_one_block(const KvView& kv, bool paged, int group, const TopkCall& call, const MlpView* phi,
+                                       const uint16_t* q, hipStream_t stream)
+{
+    if (call.max_seq_len > score_topk_one_block_limit()) return hipErrorInvalidValue;
+    OneBlockEncode enc;
+    if (phi) {
+        if (!one_block_can_encode(*phi) || !q) return hipErrorInvalidValue;
+        enc.n_layers = phi->n_layers;
+        enc.phi = *phi;
+        enc.q = q;
+    }
+    return paged ? one_block_by_length<true>(false, kv, group, call, enc, stream)
+                 : one_block_by_length<false>(false, kv, group, call, enc, stream);
 }
 
 hipError_t launch_score_topk(const KvView& kv, bool paged, int group, const TopkCall& call, int unit_tokens,

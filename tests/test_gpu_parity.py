@@ -84,6 +84,34 @@ def check_gather(D, ocache, idx_dev, count_dev, ref_topk, heads=None):
     return out
 
 
+def check_combined_entry(D, qc_ref, act_q, ref, n_sink=0, n_local=0, min_compared=0.9):
+    """hashattn_encode_score_topk on the device's current key codes (the oracle's): its query codes against
+    the oracle's where the activation decides the bit, and for every head whose code is the oracle's, ids,
+    count and threshold against `ref` (the oracle's result for the oracle's codes)."""
+    pitch = D.k_max + n_sink + n_local
+    idx = torch.full((D.B, D.Hq, pitch), -7, dtype=torch.int32, device=gu.DEV)
+    count = torch.full((D.B, D.Hq), -7, dtype=torch.int32, device=gu.DEV)
+    thr = torch.full((D.B, D.Hq), 255, dtype=torch.uint8, device=gu.DEV)
+    qc = torch.zeros((D.B, D.Hq), dtype=torch.int32, device=gu.DEV)
+    D.ctx.hashattn_encode_score_topk(D.phi_q, D.q, D.cache, D.B, D.k_per_seq, D.k_max, n_sink, n_local, qc, idx, count, thr)
+    torch.cuda.synchronize()
+    qc_h, idx_h, count_h, thr_h = gu.u32_host(qc), idx.cpu().numpy(), count.cpu().numpy(), thr.cpu().numpy()
+    flips = gu.assert_codes_match(qc_h, qc_ref, act_q, "query codes (combined entry point)")
+    compared = 0
+    for (b, h), (want, T) in ref.items():
+        if qc_h[b, h] != qc_ref[b, h]:
+            continue                                   # a bit within rounding of zero: another query code, another set
+        compared += 1
+        assert count_h[b, h] == len(want), (b, h, count_h[b, h], len(want))
+        np.testing.assert_array_equal(idx_h[b, h, :len(want)], want, err_msg=f"combined entry: idx of (b={b}, h={h})")
+        assert np.all(idx_h[b, h, len(want):] == -7)
+        if len(want):
+            assert thr_h[b, h] == T
+    assert len(ref) - compared <= max(2, (1 - min_compared) * len(ref)), \
+        f"only {compared} of {len(ref)} heads had the oracle's query code"
+    return flips
+
+
 # ---------------------------------------------------------------- C0: single head, random codes
 def test_c0_score_topk_and_gather():
     L = W.make_layer(W.c0())
@@ -306,6 +334,7 @@ def run_whole_step(L, extra_rows=0, gather_heads=None):
     ref = oracle_topk_all(codes, lens, qc_ref, L.k_per_seq, g, L)
     idx, count = check_topk(D, qc_ref, ref)
     out_staged = check_gather(D, ocache, idx, count, ref, heads=gather_heads)
+    flips += check_combined_entry(D, qc_ref, act_q, ref)
 
     # chained GPU step on the GPU's own codes
     D.set_codes(gpu_codes_after)

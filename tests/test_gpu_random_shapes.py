@@ -7,7 +7,7 @@ import pytest
 
 from test_gpu_window import window_case
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("topk_path")]
 
 
 def draw_case(rng):

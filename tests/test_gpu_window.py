@@ -11,7 +11,7 @@ import oracle
 import workloads as W
 import gpu_util as gu
 
-pytestmark = pytest.mark.gpu
+pytestmark = [pytest.mark.gpu, pytest.mark.usefixtures("topk_path")]
 
 
 def random_codes(rng):
