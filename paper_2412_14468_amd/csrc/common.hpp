@@ -145,18 +145,25 @@ __device__ __forceinline__ unsigned lowest_bits(unsigned x, int take)
 
 // Token ids of the set bits of m (bit p = token t0 + p), written to out[rank], out[rank + 1], ...
 // At 1/32 density a lane rarely holds more than three of its sixteen tokens: three rounds without a
-// branch (a lane with nothing left just does not store), then a loop for the rest.
+// branch (a lane with nothing left just does not store), then a loop for the rest.  Ranks stay below
+// the row's pitch when the counts that produced them match the codes; a mask that would pass it is cut
+// to the room that is left, once, so that the rounds need no check of their own.  `out` is the same
+// for the whole wave.
 __device__ __forceinline__ void emit_ids(unsigned m, int rank, int t0, int pitch, int32_t* __restrict__ out)
 {
-    auto round = [&]() {
-        if (m != 0u && rank < pitch) out[rank] = t0 + (__ffs((int)m) - 1);
-        rank += m != 0u ? 1 : 0;
-        m &= m - 1u;                                   // clears the lowest set bit; 0 stays 0
-    };
-    round();
-    round();
-    round();
-    while (__builtin_amdgcn_ballot_w64(m != 0u) != 0ull) round();
+    const int room = pitch - rank;
+    if (__builtin_amdgcn_ballot_w64(__popc(m) > room) != 0ull) m = lowest_bits(m, max(room, 0));
+    int32_t* p = out + (unsigned)max(rank, 0);          // the lane's ids go to p[0], p[1], ...: one address, constant offsets
+    const unsigned m1 = m & (m - 1u), m2 = m1 & (m1 - 1u);        // m without its lowest one / two set bits; 0 stays 0
+    if (m != 0u) p[0] = t0 + (__ffs((int)m) - 1);
+    if (m1 != 0u) p[1] = t0 + (__ffs((int)m1) - 1);
+    if (m2 != 0u) p[2] = t0 + (__ffs((int)m2) - 1);
+    m = m2 & (m2 - 1u);
+    p += 3;
+    while (__builtin_amdgcn_ballot_w64(m != 0u) != 0ull) {
+        if (m != 0u) *p++ = t0 + (__ffs((int)m) - 1);
+        m &= m - 1u;
+    }
 }
 
 // Workgroups go to the eight XCDs round-robin in launch order, x fastest.  With the piece index
