@@ -615,7 +615,11 @@ __global__ __launch_bounds__(kOneWaves * kWave) void score_topk_one_block_kernel
     extern __shared__ uint4 lds_all[];                          // kOneLdsPerWave bytes per wave
     __shared__ int wbins[kOneWaves][kCumRow];                   // per wave: #{score == s}, slot 33 = 0
     const int tid = threadIdx.x, wave = uniform(tid >> 6), lane = tid & 63;
-    const int h = blockIdx.x, b = blockIdx.y, kvh = h / group;
+    // workgroups go to the eight XCDs round-robin: numbering the heads KV head first puts the query heads of a
+    // group n_kv_heads numbers apart, on one XCD when that is a multiple of eight, so that the group's codes
+    // come from memory once and from that XCD's L2 afterwards
+    const int n_kv_heads = n_q_heads / group;
+    const int kvh = blockIdx.x % n_kv_heads, h = kvh * group + blockIdx.x / n_kv_heads, b = blockIdx.y;
     const int64_t bh = (int64_t)b * n_q_heads + h;
     unsigned* whist = reinterpret_cast<unsigned*>(reinterpret_cast<char*>(lds_all) + wave * kOneLdsPerWave);
 
