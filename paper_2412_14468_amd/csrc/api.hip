@@ -149,6 +149,10 @@ int pick_unit_tokens(const hashattn_ctx* ctx, int batch, int max_seq_len, bool m
         int unit = kMinUnit;
         // up to about one block per CU keeps the per-block tables short
         while (unit < cap && lanes * blocks(unit) > 256) unit *= 2;
+        // units of 2048 tokens (two chunks per wave in the select, 92 registers: two 8-wave blocks per CU) only
+        // where units of 1024 (75 registers: three blocks per CU) would mean more than 2048 blocks (few pairs at a very
+        // long context take 16-wave blocks instead, below)
+        if (unit == kMaxUnit && !wide && lanes > 16 && lanes * blocks(kMaxUnit / 2) <= 2048) unit = kMaxUnit / 2;
         // never more blocks per sequence than the scratch pitch
         while (unit < hard_cap && blocks(unit) > ctx->blocks_pitch) unit *= 2;
         return unit;

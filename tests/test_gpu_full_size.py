@@ -164,28 +164,29 @@ def test_c4_full_size_sampled_pairs_paged():
     run_sampled(cfg, W.BASE_SEED + 4004, [(longest, 2), (shortest, 5), (31, 0)])
 
 
-def codes_only_case(n, k, Hq, Hkv, seed):
+def codes_only_case(n, k, Hq, Hkv, seed, batch=1):
     """SCORE + TOPK on uniform random codes (K/V are not touched), every query head against the oracle."""
     import paper_2412_14468_amd as ha
     import gpu_util as gu
     rng = np.random.default_rng(seed)
-    codes = rng.integers(0, 2 ** 32, size=(1, Hkv, n), dtype=np.uint64).astype(np.uint32)
-    q_codes = rng.integers(0, 2 ** 32, size=(1, Hq), dtype=np.uint64).astype(np.uint32)
-    kz = torch.zeros((1, Hkv, 4, 128), dtype=torch.bfloat16, device=DEV)
-    cache = ha.KvCache(kz, kz, gu.u32_dev(codes), torch.tensor([n], dtype=torch.int32, device=DEV), n)
+    codes = rng.integers(0, 2 ** 32, size=(batch, Hkv, n), dtype=np.uint64).astype(np.uint32)
+    q_codes = rng.integers(0, 2 ** 32, size=(batch, Hq), dtype=np.uint64).astype(np.uint32)
+    kz = torch.zeros((batch, Hkv, 4, 128), dtype=torch.bfloat16, device=DEV)
+    cache = ha.KvCache(kz, kz, gu.u32_dev(codes), torch.full((batch,), n, dtype=torch.int32, device=DEV), n)
     cache.c.n_max = n                                                         # the code store has n rows
-    ctx = ha.Context(Hq, Hkv, 1, n, k)
-    idx = torch.full((1, Hq, k), -7, dtype=torch.int32, device=DEV)
-    count = torch.zeros((1, Hq), dtype=torch.int32, device=DEV)
-    thr = torch.zeros((1, Hq), dtype=torch.uint8, device=DEV)
-    ctx.hashattn_score_topk(gu.u32_dev(q_codes), cache, 1, None, k, idx, count, thr)
+    ctx = ha.Context(Hq, Hkv, batch, n, k)
+    idx = torch.full((batch, Hq, k), -7, dtype=torch.int32, device=DEV)
+    count = torch.zeros((batch, Hq), dtype=torch.int32, device=DEV)
+    thr = torch.zeros((batch, Hq), dtype=torch.uint8, device=DEV)
+    ctx.hashattn_score_topk(gu.u32_dev(q_codes), cache, batch, None, k, idx, count, thr)
     torch.cuda.synchronize()
-    idx_h = idx.cpu().numpy()
-    for h in range(Hq):
-        sc = oracle.scores(int(q_codes[0, h]), codes[0, h // (Hq // Hkv)])
-        ref, rthr = oracle.topk_hist(sc, k)
-        assert int(count[0, h]) == k and int(thr[0, h]) == rthr
-        np.testing.assert_array_equal(idx_h[0, h], ref)
+    idx_h, count_h, thr_h = idx.cpu().numpy(), count.cpu().numpy(), thr.cpu().numpy()
+    for b in range(batch):
+        for h in range(Hq):
+            sc = oracle.scores(int(q_codes[b, h]), codes[b, h // (Hq // Hkv)])
+            ref, rthr = oracle.topk_hist(sc, k)
+            assert int(count_h[b, h]) == k and int(thr_h[b, h]) == rthr
+            np.testing.assert_array_equal(idx_h[b, h], ref)
 
 
 def test_topk_at_the_context_limit():
@@ -201,3 +202,9 @@ def test_topk_at_the_context_limit():
 def test_topk_groups_of_eight_at_512k():
     """64 query heads on 8 KV heads at 512K tokens: units of 2048 tokens with eight heads per block."""
     codes_only_case(524288, 16384, 64, 8, W.BASE_SEED + 4097)
+
+
+def test_topk_many_sequences_units_of_2048():
+    """130 sequences of 140000 tokens: 8-wave blocks of 1024-token units would be more than 2048 blocks, so the
+    units are 2048 tokens (two chunks per wave in the select)."""
+    codes_only_case(140000, 4375, 2, 1, W.BASE_SEED + 4098, batch=130)
