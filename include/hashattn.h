@@ -211,6 +211,32 @@ hashattn_status hashattn_encode_score_topk(hashattn_ctx* ctx, const hashattn_mlp
                                            int32_t* idx, int32_t* count, uint8_t* threshold,
                                            void* stream);
 
+/* One decode step of a layer in one call (section 4; section 4.1): [the new
+ * token enters the cache as in hashattn_encode_keys with n_new = 1,] the query
+ * is encoded, scored against every cached key (the new one included), the
+ * top-k tokens are selected as in hashattn_score_topk_window, and GATHER-ATT
+ * runs over them.  The results are those of the separate calls in that order;
+ * the call exists so that the library can share launches between the steps
+ * (append and query encoding in one launch when both mappings have one of the
+ * shapes 128 -> 32, 128 -> 128 -> 32, 128 -> 128 -> 128 -> 32; query encoding,
+ * SCORE and TOPK in one launch for short contexts, see
+ * hashattn_encode_score_topk).
+ *   k_new, v_new  dev bf16 [batch][H_kv][128], or both NULL: nothing is appended
+ *                 and phi_kv is not read
+ *   cache         as in hashattn_encode_keys: seq_lens and max_seq_len advance
+ *                 by one when a token is appended
+ *   scale         softmax scale, 1 / sqrt(128) for section 3.1's attention
+ *   q_codes, idx, count, threshold   outputs as in hashattn_encode_score_topk
+ *   out           dev bf16 [batch][n_q_heads][128]
+ * Errors as in the separate calls; a step that fails after the append has been
+ * launched leaves the token appended. */
+hashattn_status hashattn_decode_step(hashattn_ctx* ctx, const hashattn_mlp* phi_kv, const void* k_new,
+                                     const void* v_new, const hashattn_mlp* phi_q, const void* q,
+                                     hashattn_kv* cache, int32_t batch, const int32_t* k_per_seq,
+                                     int32_t k_max, int32_t n_sink, int32_t n_local, float scale,
+                                     uint32_t* q_codes, int32_t* idx, int32_t* count, uint8_t* threshold,
+                                     void* out, void* stream);
+
 /* GATHER-ATT (section 4): softmax attention over the selected tokens only,
  *   out[b][h] = sum_{i in I} softmax_i(scale * <q, k_i>) v_i,
  * normalised over the selected tokens, fp32 accumulation, bf16 result.

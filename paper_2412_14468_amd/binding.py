@@ -80,6 +80,9 @@ def load() -> C.CDLL:
     L.hashattn_score_topk_window.argtypes = [vp, vp, C.POINTER(KvStruct), i32, vp, i32, i32, i32, vp, vp, vp, vp]
     L.hashattn_encode_score_topk.restype = i32
     L.hashattn_encode_score_topk.argtypes = [vp, C.POINTER(MlpStruct), vp, C.POINTER(KvStruct), i32, vp, i32, i32, i32, vp, vp, vp, vp, vp]
+    L.hashattn_decode_step.restype = i32
+    L.hashattn_decode_step.argtypes = [vp, C.POINTER(MlpStruct), vp, vp, C.POINTER(MlpStruct), vp, C.POINTER(KvStruct), i32, vp,
+                                       i32, i32, i32, C.c_float, vp, vp, vp, vp, vp, vp]
     L.hashattn_gather_attend.restype = i32
     L.hashattn_gather_attend.argtypes = [vp, vp, C.POINTER(KvStruct), vp, vp, i32, i32, C.c_float, vp, vp]
     L.hashattn_gather_attend_noalloc.restype = i32
@@ -228,6 +231,14 @@ class Context:
         self._check(load().hashattn_encode_score_topk(self.h, C.byref(phi_q.c), _ptr(q), C.byref(cache.c), batch,
                                                       _ptr(k_per_seq), k_max, n_sink, n_local, _ptr(q_codes), _ptr(idx),
                                                       _ptr(count), _ptr(threshold), _stream(stream)))
+
+    def hashattn_decode_step(self, phi_kv: Optional[Mlp], k_new, v_new, phi_q: Mlp, q, cache: KvCache, batch: int, k_per_seq,
+                             k_max: int, n_sink: int, n_local: int, scale: float, q_codes, idx, count, threshold, out,
+                             stream=None) -> None:
+        self._check(load().hashattn_decode_step(self.h, C.byref(phi_kv.c) if phi_kv is not None else None, _ptr(k_new),
+                                                _ptr(v_new), C.byref(phi_q.c), _ptr(q), C.byref(cache.c), batch,
+                                                _ptr(k_per_seq), k_max, n_sink, n_local, float(scale), _ptr(q_codes),
+                                                _ptr(idx), _ptr(count), _ptr(threshold), _ptr(out), _stream(stream)))
 
     def hashattn_gather_attend(self, q, cache: KvCache, idx, count, batch: int, k_max: int, scale: float, out,
                                stream=None) -> None:

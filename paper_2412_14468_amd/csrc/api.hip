@@ -452,6 +452,62 @@ hashattn_status hashattn_encode_score_topk(hashattn_ctx* ctx, const hashattn_mlp
     return e == hipSuccess ? HASHATTN_OK : hip_fail(ctx, e, "encode_score_topk");
 }
 
+hashattn_status hashattn_decode_step(hashattn_ctx* ctx, const hashattn_mlp* phi_kv, const void* k_new, const void* v_new,
+                                     const hashattn_mlp* phi_q, const void* q, hashattn_kv* cache, int32_t batch,
+                                     const int32_t* k_per_seq, int32_t k_max, int32_t n_sink, int32_t n_local, float scale,
+                                     uint32_t* q_codes, int32_t* idx, int32_t* count, uint8_t* threshold, void* out,
+                                     void* stream)
+{
+    if (!ctx) return HASHATTN_INVALID_ARG;
+    if ((k_new == nullptr) != (v_new == nullptr))
+        return fail(ctx, HASHATTN_INVALID_ARG, "decode_step: k_new and v_new must both be given (append) or both NULL");
+    bool encoded = false;
+    if (k_new) {
+        // the append and the query encoding share a launch when both mappings have the same fixed shape and
+        // the query encoding is not going to be folded into the SCORE + TOPK launch anyway
+        const bool share = phi_kv && phi_q && cache && q && q_codes && ctx->cfg.bits == ha::kBits &&
+                           phi_kv->n_layers >= 1 && phi_kv->n_layers <= 4 && phi_q->n_layers >= 1 && phi_q->n_layers <= 4 &&
+                           ha::encode_step_supported(view_of(phi_kv), view_of(phi_q)) &&
+                           !one_launch_topk(ctx, batch, cache->max_seq_len + 1);
+        if (!share) {
+            if (hashattn_status s = hashattn_encode_keys(ctx, phi_kv, k_new, v_new, batch, 1, cache, stream)) return s;
+        } else {
+            if (hashattn_status s = check_append_state(ctx, "decode_step")) return s;
+            if (hashattn_status s = check_mlp(ctx, phi_kv, ctx->cfg.n_kv_heads, "decode_step")) return s;
+            if (hashattn_status s = check_mlp(ctx, phi_q, ctx->cfg.n_q_heads, "decode_step")) return s;
+            if (hashattn_status s = check_cache(ctx, cache, batch, true, "decode_step")) return s;
+            if (!aligned(k_new, 16) || !aligned(v_new, 16) || !aligned(q, 16) || !aligned(q_codes, 4))
+                return fail(ctx, HASHATTN_INVALID_ARG, "decode_step: k_new, v_new and q need 16-byte, q_codes 4-byte alignment");
+            const bool paged = ctx->cfg.page_size != 0;
+            const int64_t room = paged ? (int64_t)cache->max_pages_per_seq * ha::kPage : cache->n_max;
+            if ((int64_t)cache->max_seq_len + 1 > room)
+                return fail(ctx, HASHATTN_INVALID_ARG, "decode_step: appending a token to max_seq_len %d exceeds the cache capacity %lld",
+                            cache->max_seq_len, (long long)room);
+            if ((int64_t)cache->max_seq_len + 1 > ctx->cfg.max_context)
+                return fail(ctx, HASHATTN_SCRATCH_TOO_SMALL, "decode_step: append would exceed max_context %lld", (long long)ctx->cfg.max_context);
+            const ha::EncodeScratch enc{ctx->frags, ha::encode_mfma_scratch_bytes_per_head() / 16, ctx->append_done,
+                                        ctx->append_fault_dev};
+            const hipError_t e = ha::launch_encode_step(view_of(phi_kv), view_of(phi_q), view_of(ctx, cache), paged,
+                                                        ctx->cfg.n_q_heads, static_cast<const uint16_t*>(k_new),
+                                                        static_cast<const uint16_t*>(v_new), static_cast<const uint16_t*>(q), batch,
+                                                        q_codes, cache->max_seq_len, enc, static_cast<hipStream_t>(stream));
+            if (e != hipSuccess) return hip_fail(ctx, e, "decode_step");
+            cache->max_seq_len += 1;
+            encoded = true;
+        }
+    }
+    if (encoded) {
+        if (hashattn_status s = hashattn_score_topk_window(ctx, q_codes, cache, batch, k_per_seq, k_max, n_sink, n_local, idx,
+                                                           count, threshold, stream))
+            return s;
+    } else {
+        if (hashattn_status s = hashattn_encode_score_topk(ctx, phi_q, q, cache, batch, k_per_seq, k_max, n_sink, n_local,
+                                                           q_codes, idx, count, threshold, stream))
+            return s;
+    }
+    return hashattn_gather_attend(ctx, q, cache, idx, count, batch, k_max + n_sink + n_local, scale, out, stream);
+}
+
 hashattn_status hashattn_gather_attend(hashattn_ctx* ctx, const void* q, const hashattn_kv* cache, const int32_t* idx,
                                        const int32_t* count, int32_t batch, int32_t k_max, float scale, void* out,
                                        void* stream)

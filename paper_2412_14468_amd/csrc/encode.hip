@@ -165,13 +165,12 @@ __device__ __forceinline__ uint32_t append_base(const uint32_t* __restrict__ sta
 }
 
 __device__ __forceinline__ void finish_append(uint32_t* __restrict__ state, uint32_t base, int32_t* __restrict__ fault,
-                                              int32_t* __restrict__ seq_lens, int batch, int n_new)
+                                              int32_t* __restrict__ seq_lens, int batch, int n_new, uint32_t total)
 {
     __shared__ int last;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's length (and the base) have arrived
     __syncthreads();                                   // all threads of the block have read seq_lens
-    if (threadIdx.x == 0) {
-        const uint32_t total = gridDim.x * gridDim.y;
+    if (threadIdx.x == 0) {                            // total: blocks of this launch that append
         const uint32_t mine = atomicAdd(state, 1u) - base;
         last = mine == total - 1u;
         if (last) __hip_atomic_store(state + 1, base + total, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -201,7 +200,7 @@ __global__ __launch_bounds__(256) void encode_vec_kernel(MlpView phi, int n_head
         const uint32_t base = append_base(done);
         pos = append_position<kVecPerBlock>(c, v0, n_vec, n_new, n_cap);
         piece = append_piece<kVecPerBlock>(x, v_new, n_heads, head, v0, n_vec, n_new);
-        finish_append(done, base, fault, c.seq_lens, n_vec / n_new, n_new);
+        finish_append(done, base, fault, c.seq_lens, n_vec / n_new, n_new, gridDim.x * gridDim.y);
     }
     load_vectors<MODE, kMaxWidth, kVecPerBlock>(act[0], n_heads, head, v0, x, n_vec, n_new);
     __syncthreads();
@@ -251,21 +250,15 @@ __device__ __forceinline__ void gemv_layer(const float (&w)[DI * DOUT / 256], co
     __syncthreads();
 }
 
-// NL layers: 128 -> D1 -> D2 -> 32 (NL = 3), 128 -> D1 -> 32 (NL = 2), 128 -> 32 (NL = 1).
-// VT vectors per block: every vector costs a block its LDS reads and multiplies one after the other, so
-// a launch with few vectors spreads them over more blocks (the weights are then read VT times less often
-// than once per vector, from L2 after the first block of a head).
+// One block's work: `head` and the vectors v0 .. v0 + VT - 1.  append_blocks: blocks of the launch that append
+// (MODE 1; the count that moves the sequence lengths runs over them).
 template <int MODE, bool PAGED, int NL, int D1, int D2, int VT>
-__global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int n_heads,
-                                                               const uint16_t* __restrict__ x,
-                                                               const uint16_t* __restrict__ v_new, int n_vec,
-                                                               int n_new, uint32_t* __restrict__ q_codes,
-                                                               KvView c, int n_cap, uint32_t* __restrict__ done,
-                                                               int32_t* __restrict__ fault)
+__device__ __forceinline__ void encode_fixed_block(const MlpView& phi, int n_heads, int head, int v0,
+                                                   const uint16_t* __restrict__ x, const uint16_t* __restrict__ v_new,
+                                                   int n_vec, int n_new, uint32_t* __restrict__ q_codes, const KvView& c,
+                                                   int n_cap, uint32_t* __restrict__ done, int32_t* __restrict__ fault,
+                                                   uint32_t append_blocks, float (*act)[VT][kFixedWidth], float* red)
 {
-    __shared__ float act[2][VT][kFixedWidth];
-    __shared__ float red[VT * 256];
-    const int head = blockIdx.x, v0 = blockIdx.y * VT;
     constexpr int O0 = NL == 1 ? kBits : D1;            // outputs of layer 0
     constexpr int I1 = D1, O1 = NL == 2 ? kBits : D2;   // layer 1 (NL >= 2)
     constexpr int I2 = D2;                              // layer 2 (NL == 3), 32 outputs
@@ -282,7 +275,7 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
         const uint32_t base = append_base(done);
         pos = append_position<VT>(c, v0, n_vec, n_new, n_cap);
         piece = append_piece<VT>(x, v_new, n_heads, head, v0, n_vec, n_new);
-        finish_append(done, base, fault, c.seq_lens, n_vec / n_new, n_new);
+        finish_append(done, base, fault, c.seq_lens, n_vec / n_new, n_new, append_blocks);
     }
     __syncthreads();
     gemv_layer<kHeadDim, O0, VT>(w0, phi.bias[0] ? phi.bias[0] + (int64_t)head * O0 : nullptr, act[0], act[1], red, NL == 1);
@@ -291,6 +284,48 @@ __global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int 
     if constexpr (NL == 3)
         gemv_layer<I2, kBits, VT>(w2, phi.bias[2] ? phi.bias[2] + (int64_t)head * kBits : nullptr, act[0], act[1], red, true);
     store_codes<MODE, PAGED, kFixedWidth, VT>(act[NL & 1], n_heads, head, v0, x, v_new, n_vec, n_new, q_codes, c, pos, piece);
+}
+
+// NL layers: 128 -> D1 -> D2 -> 32 (NL = 3), 128 -> D1 -> 32 (NL = 2), 128 -> 32 (NL = 1).
+// VT vectors per block: every vector costs a block its LDS reads and multiplies one after the other, so
+// a launch with few vectors spreads them over more blocks (the weights are then read VT times less often
+// than once per vector, from L2 after the first block of a head).
+template <int MODE, bool PAGED, int NL, int D1, int D2, int VT>
+__global__ __launch_bounds__(256) void encode_vec_fixed_kernel(MlpView phi, int n_heads,
+                                                               const uint16_t* __restrict__ x,
+                                                               const uint16_t* __restrict__ v_new, int n_vec,
+                                                               int n_new, uint32_t* __restrict__ q_codes,
+                                                               KvView c, int n_cap, uint32_t* __restrict__ done,
+                                                               int32_t* __restrict__ fault)
+{
+    __shared__ float act[2][VT][kFixedWidth];
+    __shared__ float red[VT * 256];
+    encode_fixed_block<MODE, PAGED, NL, D1, D2, VT>(phi, n_heads, blockIdx.x, blockIdx.y * VT, x, v_new, n_vec, n_new, q_codes,
+                                                    c, n_cap, done, fault, gridDim.x * gridDim.y, act, red);
+}
+
+// The decode step's two mappings in one launch: the first append_blocks blocks append one token per sequence
+// (its K/V rows, its key code, the sequence lengths), the others encode the queries.  Both mappings have the
+// same fixed shape.  Block i of a role takes head i % heads and the vectors (i / heads) VT ...
+template <bool PAGED, int NL, int D1, int D2, int VT>
+__global__ __launch_bounds__(256) void encode_step_kernel(MlpView phi_kv, MlpView phi_q, int n_kv_heads, int n_q_heads,
+                                                          const uint16_t* __restrict__ k_new,
+                                                          const uint16_t* __restrict__ v_new,
+                                                          const uint16_t* __restrict__ q, int batch,
+                                                          uint32_t* __restrict__ q_codes, KvView c, int n_cap,
+                                                          uint32_t* __restrict__ done, int32_t* __restrict__ fault,
+                                                          int append_blocks)
+{
+    __shared__ float act[2][VT][kFixedWidth];
+    __shared__ float red[VT * 256];
+    const int i = blockIdx.x;
+    if (i < append_blocks)
+        encode_fixed_block<1, PAGED, NL, D1, D2, VT>(phi_kv, n_kv_heads, i % n_kv_heads, (i / n_kv_heads) * VT, k_new, v_new, batch,
+                                                     1, nullptr, c, n_cap, done, fault, (uint32_t)append_blocks, act, red);
+    else
+        encode_fixed_block<0, PAGED, NL, D1, D2, VT>(phi_q, n_q_heads, (i - append_blocks) % n_q_heads,
+                                                     ((i - append_blocks) / n_q_heads) * VT, q, nullptr, batch, 1, q_codes, c,
+                                                     n_cap, nullptr, nullptr, 0u, act, red);
 }
 
 template <int MODE, bool PAGED, int NL, int D1, int D2>
@@ -486,6 +521,63 @@ hipError_t setup_encode_bulk()
 hipError_t launch_set_append_counter(uint32_t* state, uint32_t value, hipStream_t stream)
 {
     set_append_counter_kernel<<<1, 1, 0, stream>>>(state, value);
+    return hipGetLastError();
+}
+
+namespace {
+
+template <bool PAGED, int NL, int D1, int D2>
+void launch_step_fixed(int vt, const MlpView& phi_kv, const MlpView& phi_q, const KvView& kv, int n_q_heads,
+                       const uint16_t* k_new, const uint16_t* v_new, const uint16_t* q, int batch, uint32_t* q_codes,
+                       int n_cap, const EncodeScratch& sc, hipStream_t stream)
+{
+    const int per_role = (batch + vt - 1) / vt;
+    const int append_blocks = kv.n_kv_heads * per_role, blocks = append_blocks + n_q_heads * per_role;
+#define HA_STEP(VT) encode_step_kernel<PAGED, NL, D1, D2, VT><<<blocks, 256, 0, stream>>>(phi_kv, phi_q, kv.n_kv_heads, n_q_heads, k_new, v_new, q, batch, q_codes, kv, n_cap, sc.append_done, sc.append_fault, append_blocks)
+    switch (vt) {
+    case 1: HA_STEP(1); break;
+    case 2: HA_STEP(2); break;
+    case 4: HA_STEP(4); break;
+    default: HA_STEP(8); break;
+    }
+#undef HA_STEP
+}
+
+// 1, 2 or 3 when the mapping has one of the fixed shapes of the vector kernels (128 -> 32, 128 -> 128 -> 32,
+// 128 -> 128 -> 128 -> 32), else 0
+int fixed_shape(const MlpView& phi)
+{
+    if (phi.dims[0] != kHeadDim || phi.dims[phi.n_layers] != kBits) return 0;
+    if (phi.n_layers == 1) return 1;
+    if (phi.n_layers == 2 && phi.dims[1] == 128) return 2;
+    if (phi.n_layers == 3 && phi.dims[1] == 128 && phi.dims[2] == 128) return 3;
+    return 0;
+}
+
+}  // namespace
+
+bool encode_step_supported(const MlpView& phi_kv, const MlpView& phi_q)
+{
+    const int a = fixed_shape(phi_kv);
+    return a != 0 && a == fixed_shape(phi_q);
+}
+
+// One token per sequence appended (rows, key code, lengths) and the queries encoded, in one launch.
+hipError_t launch_encode_step(const MlpView& phi_kv, const MlpView& phi_q, const KvView& kv, bool paged, int n_q_heads,
+                              const uint16_t* k_new, const uint16_t* v_new, const uint16_t* q, int batch,
+                              uint32_t* q_codes, int max_seq_len, const EncodeScratch& sc, hipStream_t stream)
+{
+    if (!encode_step_supported(phi_kv, phi_q)) return hipErrorInvalidValue;
+    // vectors per block as for a query launch of its own (the role with more heads decides)
+    int vt = batch == 1 ? 1 : 2;
+    while (vt < kVecPerBlock && (int64_t)n_q_heads * ((batch + vt - 1) / vt) > 512) vt *= 2;
+    const int nl = fixed_shape(phi_q);
+#define HA_STEP_NL(P) \
+    if (nl == 1) launch_step_fixed<P, 1, 32, 32>(vt, phi_kv, phi_q, kv, n_q_heads, k_new, v_new, q, batch, q_codes, max_seq_len, sc, stream); \
+    else if (nl == 2) launch_step_fixed<P, 2, 128, 32>(vt, phi_kv, phi_q, kv, n_q_heads, k_new, v_new, q, batch, q_codes, max_seq_len, sc, stream); \
+    else launch_step_fixed<P, 3, 128, 128>(vt, phi_kv, phi_q, kv, n_q_heads, k_new, v_new, q, batch, q_codes, max_seq_len, sc, stream)
+    if (paged) { HA_STEP_NL(true); } else { HA_STEP_NL(false); }
+#undef HA_STEP_NL
     return hipGetLastError();
 }
 

@@ -37,6 +37,12 @@ hipError_t launch_encode_keys(const MlpView& phi, const KvView& kv, bool paged,
                               const uint16_t* k_new, const uint16_t* v_new,
                               int batch, int64_t n_new, int max_seq_len, const EncodeScratch* sc,
                               hipStream_t stream);
+// The decode step's append (one token per sequence: rows, key code, lengths) and its query encoding in one
+// launch, for mappings of one of the fixed shapes of the vector kernels, the same for keys and queries.
+bool encode_step_supported(const MlpView& phi_kv, const MlpView& phi_q);
+hipError_t launch_encode_step(const MlpView& phi_kv, const MlpView& phi_q, const KvView& kv, bool paged, int n_q_heads,
+                              const uint16_t* k_new, const uint16_t* v_new, const uint16_t* q, int batch,
+                              uint32_t* q_codes, int max_seq_len, const EncodeScratch& sc, hipStream_t stream);
 
 hipError_t setup_encode_bulk();
 hipError_t launch_set_append_counter(uint32_t* state, uint32_t value, hipStream_t stream);

@@ -60,17 +60,19 @@ def build_key_codes(ctx: Context, s: LayerState) -> None:
 
 
 def decode_step(ctx: Context, s: LayerState, append: bool = False, separate_calls: bool = False) -> None:
-    """[append] -> encode query + SCORE + TOPK -> GATHER-ATT, all on torch's current stream.  separate_calls:
-    the query encoder and SCORE + TOPK through their own entry points instead of the combined one."""
+    """[append] -> encode query -> SCORE + TOPK -> GATHER-ATT on torch's current stream: one call of
+    hashattn_decode_step, or (separate_calls, or a layer without a query mapping) the entry points of the steps
+    one after the other."""
+    if s.phi_q is not None and not separate_calls:
+        ctx.hashattn_decode_step(s.phi_kv if append else None, s.k_new if append else None, s.v_new if append else None,
+                                 s.phi_q, s.q, s.cache, s.B, s.k_per_seq, s.k_max, s.n_sink, s.n_local, s.scale,
+                                 s.q_codes, s.idx, s.count, s.threshold, s.out)
+        return
     if append:
         ctx.hashattn_encode_keys(s.phi_kv, s.k_new, s.v_new, s.B, 1, s.cache)
-    if s.phi_q is not None and not separate_calls:
-        ctx.hashattn_encode_score_topk(s.phi_q, s.q, s.cache, s.B, s.k_per_seq, s.k_max, s.n_sink, s.n_local,
-                                       s.q_codes, s.idx, s.count, s.threshold)
-    else:
-        if s.phi_q is not None:
-            ctx.hashattn_encode_query(s.phi_q, s.q, s.B, s.q_codes)
-        score_topk(ctx, s)
+    if s.phi_q is not None:
+        ctx.hashattn_encode_query(s.phi_q, s.q, s.B, s.q_codes)
+    score_topk(ctx, s)
     gather_attend(ctx, s)
 
 
