@@ -54,3 +54,7 @@ def test_null_context_is_rejected():
     assert lib.hashattn_gather_attend(None, None, None, None, None, 1, 1, 1.0, None, None) == ha.INVALID_ARG
     assert lib.hashattn_dense_attend(None, None, None, 1, 1.0, None, None) == ha.INVALID_ARG
     assert lib.hashattn_encode_keys(None, None, None, None, 1, 1, None, None) == ha.INVALID_ARG
+    assert lib.hashattn_encode_score_topk(None, None, None, None, 1, None, 1, 0, 0, None, None, None, None, None) == ha.INVALID_ARG
+    assert lib.hashattn_decode_step(None, None, None, None, None, None, None, 1, None, 1, 0, 0, 1.0, None, None, None, None,
+                                    None, None) == ha.INVALID_ARG
+    assert lib.hashattn_selftest_set_topk_path(None, 0) == ha.INVALID_ARG
