@@ -23,11 +23,13 @@ def capture(body):
     return graph
 
 
-@pytest.mark.parametrize("append", [False, True])
-def test_graph_replays_equal_eager(append):
+@pytest.mark.parametrize("append,context", [(False, 20000), (True, 20000), (False, 40000), (True, 40000)])
+def test_graph_replays_equal_eager(append, context):
+    """20000 tokens: ENCODE-Q + SCORE + TOPK in one launch; 40000: the two-launch select, and with an append the
+    launch that the append shares with the query encoder."""
     import paper_2412_14468_amd as ha
     from paper_2412_14468_amd import runner
-    cfg = W.scaled(W.c1(context=20000, k=625, batch=3), name="graph", append=append)
+    cfg = W.scaled(W.c1(context=context, k=context // 32, batch=3), name="graph", append=append)
     t = W.device_tensors(cfg, W.BASE_SEED + 99, extra_rows=4)
     s = runner.layer_from_tensors(t)
     ctx = ha.Context(cfg.n_q_heads, cfg.n_kv_heads, cfg.batch, t["n_max"], s.k_max)
